@@ -1,0 +1,112 @@
+/*
+ * escoin.h -- C ABI of the MI355X (gfx950) direct sparse convolution library.
+ *
+ * The library computes one pruned convolution layer without lowering it to a matrix
+ * product: the M x (C*R*S) filter matrix is held in CSR, one row per output channel
+ * (Section 2.3), its column indices are "stretched" once into offsets of a zero-padded
+ * 1-D input array (Section 3.1), and the output is accumulated nonzero by nonzero as in
+ * Algorithm 2.  Shape names follow Table 1: N batch, M filters / ofmap channels, C ifmap
+ * channels, H/W ifmap height/width, R/S filter height/width, E/F ofmap height/width.
+ *
+ * Conventions for every entry point
+ *   - All tensors are contiguous fp32 NCHW (filters MCRS); all indices are int32.
+ *   - Hp = H + 2*pad, Wp = W + 2*pad, E = (Hp - R)/stride + 1, F = (Wp - S)/stride + 1.
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device memory on
+ *     the current device.  The library owns no memory: every buffer is the caller's and
+ *     must stay valid until the stream work that uses it has finished.
+ *   - Device entry points enqueue on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream), never synchronise and never allocate.
+ *   - Every call returns ESCOIN_OK (0) or a negative code; nothing throws or aborts.  On an
+ *     error no kernel is launched and no output is written.
+ *   - Output buffers are overwritten (no accumulation into their previous contents) and
+ *     must not alias any input.
+ */
+#ifndef ESCOIN_H
+#define ESCOIN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct escoin_conv_desc {
+    int32_t N, C, H, W; /* input  N x C x H x W (unpadded)                     */
+    int32_t M, R, S;    /* filter M x C x R x S                                */
+    int32_t stride;     /* same stride on both axes, >= 1                      */
+    int32_t pad;        /* symmetric zero padding on all four sides, >= 0      */
+} escoin_conv_desc;
+
+enum {
+    ESCOIN_OK = 0,
+    ESCOIN_EINVAL = -1, /* null pointer, non-positive dim, malformed CSR, bad flags   */
+    ESCOIN_ERANGE = -2, /* an index would not fit int32 (C*Hp*Wp, M*E*F or nnz)       */
+    ESCOIN_EHIP = -3,   /* a HIP call (launch, attribute query) failed                */
+    ESCOIN_ESIZE = -4   /* a caller-provided buffer is too small                      */
+};
+
+enum {
+    ESCOIN_F_BIAS = 1u, /* add bias[m] to every element of output channel m          */
+    ESCOIN_F_RELU = 2u  /* clamp the result at zero: x > 0 ? x : 0                    */
+};
+
+/* Human-readable text for a return code (static storage, never NULL). */
+const char *escoin_strerror(int code);
+
+/* Validates a descriptor: ESCOIN_EINVAL for non-positive dims / stride < 1 / pad < 0 /
+ * filter larger than the padded input, ESCOIN_ERANGE when C*Hp*Wp or M*E*F reaches 2^31. */
+int escoin_check_desc(const escoin_conv_desc *desc);
+
+/* Output extent E, F (Eq. 1 generalised by padding and stride).  Returns a code. */
+int escoin_output_dims(const escoin_conv_desc *desc, int32_t *E, int32_t *F);
+
+/* Element counts of the padded input N*C*Hp*Wp and of the output N*M*E*F; 0 on a bad desc. */
+size_t escoin_padded_elems(const escoin_conv_desc *desc);
+size_t escoin_output_elems(const escoin_conv_desc *desc);
+
+/*
+ * Weight stretching (Section 3.1).  Host, pure, run once per (layer, input size).
+ * Each column index j = (c*R + r)*S + s of the M x CRS filter matrix is rewritten to the
+ * CHW layout offset f(c, r, s) = (c*Hp + r)*Wp + s of the padded input; `value` and
+ * `rowptr` are unchanged and the map is element-wise and order-preserving (entries may be
+ * in any order inside a row and may repeat).
+ *   rowptr            host, M+1 entries, rowptr[0] == 0, non-decreasing
+ *   colidx            host, nnz = rowptr[M] entries, each in [0, C*R*S)
+ *   colidx_stretched  host, nnz entries, caller-owned; may alias colidx (in-place)
+ * ESCOIN_EINVAL on a malformed CSR (nothing useful is written then).
+ */
+int escoin_sconv_pack(const escoin_conv_desc *desc, const int32_t *rowptr, const int32_t *colidx,
+                      int32_t *colidx_stretched);
+
+/*
+ * pad_in (Sections 3.1 and 4.2): the zero-padded 1-D input array
+ *   padded[n][c][y + pad][x + pad] = in[n][c][y][x], +0.0f elsewhere.
+ *   d_in      device, N*C*H*W floats
+ *   d_padded  device, N*C*Hp*Wp floats, fully overwritten
+ * With pad == 0 this is a plain copy.
+ */
+int escoin_pad_in(const escoin_conv_desc *desc, const float *d_in, float *d_padded,
+                  void *hip_stream);
+
+/*
+ * sconv, Algorithm 2 as stated, for any filter size / stride and any CSR entry order:
+ *   out[n][m][h][w] = sum over j in row m of
+ *       value[j] * padded[n][ colidx_stretched[j] + h*stride*Wp + w*stride ]
+ * optionally followed by the fused epilogue out = relu(out + bias[m]) (flags).
+ *   d_rowptr, d_colidx_stretched, d_value   device CSR (stretched by escoin_sconv_pack)
+ *   d_padded  device, N*C*Hp*Wp floats (from escoin_pad_in; the input itself when pad==0)
+ *   d_out     device, N*M*E*F floats, overwritten
+ *   d_bias    device, M floats; may be NULL unless ESCOIN_F_BIAS is set
+ * The CSR on the device is trusted (it was validated by escoin_sconv_pack): offsets outside
+ * the padded image are the caller's error.
+ */
+int escoin_sconv_forward(const escoin_conv_desc *desc, const int32_t *d_rowptr,
+                         const int32_t *d_colidx_stretched, const float *d_value,
+                         const float *d_padded, float *d_out, const float *d_bias,
+                         uint32_t flags, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESCOIN_H */

@@ -1,0 +1,73 @@
+"""Shared test plumbing: runs the HIP path through the C-ABI binding and the oracle beside it."""
+from __future__ import annotations
+
+import numpy as np
+
+TOL = 1e-4  # |gpu - oracle| <= TOL * sum|w*x| per output element (fp32 summation order is free)
+
+
+def to_dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+class DeviceLayer:
+    """CSR stretched by escoin_sconv_pack and uploaded; input uploaded; buffers allocated."""
+
+    def __init__(self, esc, L):
+        import torch
+        self.esc, self.L = esc, L
+        self.desc = esc.desc_of(L.spec)
+        self.stretched = esc.escoin_sconv_pack(self.desc, L.rowptr, L.colidx)
+        self.d_rowptr = to_dev(L.rowptr)
+        self.d_colidx = to_dev(self.stretched) if L.nnz else torch.empty(1, dtype=torch.int32, device="cuda")
+        self.d_value = to_dev(L.value) if L.nnz else torch.empty(1, dtype=torch.float32, device="cuda")
+        self.d_in = to_dev(L.input)
+        self.d_bias = to_dev(L.bias)
+        s = L.spec
+        self.d_padded = torch.empty(esc.escoin_padded_elems(self.desc), dtype=torch.float32, device="cuda")
+        self.d_out = torch.empty((s.N, s.M, s.E, s.F), dtype=torch.float32, device="cuda")
+
+    def pad(self):
+        self.d_padded.fill_(float("nan"))
+        self.esc.escoin_pad_in(self.desc, self.d_in, self.d_padded)
+        return self.d_padded
+
+    def forward(self, flags=0):
+        import torch
+        self.pad()
+        self.d_out.fill_(float("nan"))
+        self.esc.escoin_sconv_forward(self.desc, self.d_rowptr, self.d_colidx, self.d_value,
+                                      self.d_padded, self.d_out, self.d_bias, flags)
+        torch.cuda.synchronize()
+        return self.d_out.cpu().numpy()
+
+
+def oracle_full(oracle, L, flags=0):
+    s = L.spec
+    Wd = oracle.csr_to_dense(s.M, s.C, s.R, s.S, L.rowptr, L.colidx, L.value)
+    return oracle.conv(L.input, Wd, s.stride, s.pad, bias=L.bias, flags=flags)
+
+
+def assert_within_bound(got, ref, bound, what=""):
+    got = np.asarray(got, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert np.isfinite(got).all(), f"{what}: non-finite output (unwritten element?)"
+    err = np.abs(got - ref.astype(np.float64))
+    lim = TOL * bound
+    bad = err > lim
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - lim), err.shape)
+        raise AssertionError(f"{what}: {bad.sum()} of {bad.size} elements outside 1e-4*sum|w*x|; "
+                             f"worst at {i}: got {got[i]!r} ref {ref[i]!r} bound {bound[i]!r}")
+    return float((err / np.maximum(bound, 1e-30)).max())
+
+
+def sample_points(spec, k, seed):
+    """k random (n, m, h, w) plus the corners/edges of the first and last image/channel."""
+    rng = np.random.default_rng(seed)
+    pts = np.stack([rng.integers(0, spec.N, k), rng.integers(0, spec.M, k),
+                    rng.integers(0, spec.E, k), rng.integers(0, spec.F, k)], axis=1)
+    edge = [(n, m, h, w) for n in (0, spec.N - 1) for m in (0, spec.M - 1)
+            for h in (0, spec.E - 1) for w in (0, spec.F - 1)]
+    return np.concatenate([pts, np.array(edge)], axis=0).astype(np.int32)

@@ -1,0 +1,184 @@
+"""GPU parity: the HIP path (through the C-ABI binding) against the CPU oracle, element by
+element on the same seeded inputs.  Integer / copy steps are bit-exact; the fp32 convolution is
+held to |gpu - oracle| <= 1e-4 * sum|w*x| per output element."""
+import itertools
+
+import numpy as np
+import pytest
+
+import paper_1802_10280_amd as esc
+from paper_1802_10280_amd import workloads as wl
+
+from helpers import DeviceLayer, assert_within_bound, oracle_full, sample_points, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    esc.lib()   # raises if the HIP library is missing: no fallback
+
+
+# ------------------------------------------------------------------ pad_in, bit-exact
+@pytest.mark.parametrize("N,C,H,W,pad", [(1, 1, 1, 1, 0), (1, 1, 1, 1, 1), (2, 3, 5, 4, 1), (3, 5, 17, 33, 2),
+                                         (2, 7, 56, 56, 1), (1, 2, 300, 7, 3), (4, 9, 13, 13, 0)])
+def test_pad_in_bit_exact(oracle, N, C, H, W, pad):
+    import torch
+    print(f"pad_in N={N} C={C} H={H} W={W} pad={pad}", flush=True)
+    rng = np.random.default_rng(N * 100 + C)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    x.ravel()[0] = -0.0
+    d = esc.make_desc(N, C, H, W, 1, 1, 1, 1, pad)
+    d_in = to_dev(x)
+    n_pad = esc.escoin_padded_elems(d)
+    buf = torch.full((n_pad + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    esc.escoin_pad_in(d, d_in, buf[:n_pad])
+    torch.cuda.synchronize()
+    got = buf.cpu().numpy()
+    ref = oracle.pad_input(x, pad)
+    assert got[:n_pad].tobytes() == ref.tobytes()
+    assert np.isnan(got[n_pad:]).all()          # nothing written past the end
+
+
+# ------------------------------------------------------------------ sconv vs oracle, whole output
+SMALL = [
+    # N, C, H, W, M, R, S, stride, pad, sparsity
+    (1, 1, 3, 3, 1, 3, 3, 1, 0, 0.0),        # single output pixel
+    (2, 5, 9, 11, 7, 3, 3, 1, 1, 0.8),
+    (3, 16, 14, 14, 32, 3, 3, 1, 1, 0.8),
+    (2, 8, 30, 37, 5, 3, 3, 1, 1, 0.6),      # more than one pixel tile, ragged tail
+    (2, 6, 33, 35, 4, 3, 3, 2, 1, 0.7),      # stride 2
+    (2, 4, 20, 21, 6, 5, 5, 1, 2, 0.7),      # 5x5
+    (2, 24, 12, 13, 10, 1, 1, 1, 0, 0.7),    # 1x1 (CSR SpMM)
+    (1, 3, 23, 19, 3, 7, 7, 2, 3, 0.5),      # filter size with no specialisation
+    (2, 3, 10, 12, 4, 3, 3, 1, 0, 0.5),      # no padding
+    (1, 2, 9, 9, 3, 2, 3, 3, 2, 0.3),        # R != S, stride 3
+    (2, 12, 13, 13, 9, 3, 3, 1, 1, 0.0),     # dense rows (0 % sparsity)
+    (5, 20, 7, 7, 12, 3, 3, 1, 1, 0.8),      # 7x7 maps
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: "x".join(map(str, c)))
+def test_sconv_matches_oracle_small(oracle, cfg):
+    print("sconv small", cfg, flush=True)
+    N, C, H, W, M, R, S, stride, pad, sp = cfg
+    L = wl.custom_layer(N, C, H, W, M, R, S, stride, pad, sp, seed=sum(cfg[:9]) + 1, dist="normal")
+    dl = DeviceLayer(esc, L)
+    for flags in (0, esc.F_BIAS | esc.F_RELU):
+        got = dl.forward(flags)
+        ref, bound = oracle_full(oracle, L, flags)
+        assert_within_bound(got, ref, bound, f"{cfg} flags={flags}")
+
+
+def test_tiny_config_all_flag_combinations(oracle):
+    print("sconv T1 flags", flush=True)
+    L = wl.make_layer("T1")
+    dl = DeviceLayer(esc, L)
+    pad_ref = oracle.pad_input(L.input, L.spec.pad)
+    assert dl.pad().cpu().numpy().tobytes() == pad_ref.tobytes()
+    for flags in (0, esc.F_BIAS, esc.F_RELU, esc.F_BIAS | esc.F_RELU):
+        got = dl.forward(flags)
+        ref, bound = oracle_full(oracle, L, flags)
+        assert_within_bound(got, ref, bound, f"T1 flags={flags}")
+        if flags & esc.F_RELU:
+            assert (got >= 0).all()
+
+
+def test_identity_filter_reproduces_input_bit_exact():
+    """A single centre weight of 1 per output channel copies an input channel exactly."""
+    print("sconv identity", flush=True)
+    rng = np.random.default_rng(1)
+    N, C, H, W, M = 2, 6, 15, 17, 6
+    w = np.zeros((M, C, 3, 3), dtype=np.float32)
+    for m in range(M):
+        w[m, (m * 5) % C, 1, 1] = 1.0
+    rowptr, colidx, value = wl.dense_to_csr(w)
+    spec = wl.LayerSpec("ident", 9, 0, N, C, H, W, M, 3, 3, 1, 1, 0.0)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    L = wl.Layer(spec, w, rowptr, colidx, value, x, np.zeros(M, dtype=np.float32))
+    got = DeviceLayer(esc, L).forward(0)
+    for m in range(M):
+        assert got[:, m].tobytes() == x[:, (m * 5) % C].tobytes()
+
+
+def test_empty_rows_unsorted_rows_and_duplicates(oracle):
+    print("sconv empty/unsorted/duplicates", flush=True)
+    L = wl.custom_layer(2, 5, 8, 9, 6, 3, 3, 1, 1, 0.6, seed=4, dist="normal")
+    rng = np.random.default_rng(0)
+    rows = [list(zip(L.colidx[a:b], L.value[a:b])) for a, b in zip(L.rowptr[:-1], L.rowptr[1:])]
+    rows[1] = []                                            # an empty row
+    rows[5] = []                                            # last row empty
+    rows[2] = rows[2] + [(rows[2][0][0], np.float32(0.25))]  # duplicate entry
+    rows[3] = rows[3] + [(7, np.float32(0.0))]              # explicit zero
+    for r in rows:
+        rng.shuffle(r)                                      # arbitrary order inside each row
+    rowptr = np.zeros(7, dtype=np.int32)
+    rowptr[1:] = np.cumsum([len(r) for r in rows])
+    colidx = np.array([c for r in rows for c, _ in r], dtype=np.int32)
+    value = np.array([v for r in rows for _, v in r], dtype=np.float32)
+    L2 = wl.Layer(L.spec, None, rowptr, colidx, value, L.input, L.bias)
+    got = DeviceLayer(esc, L2).forward(0)
+    ref, bound = oracle_full(oracle, L2, 0)
+    assert_within_bound(got, ref, bound, "unsorted")
+    assert (got[:, 1] == 0).all() and (got[:, 5] == 0).all()
+
+
+def test_all_rows_empty_gives_bias_or_zero(oracle):
+    print("sconv nnz=0", flush=True)
+    spec = wl.LayerSpec("empty", 9, 0, 2, 3, 6, 6, 4, 3, 3, 1, 1, 1.0)
+    rng = np.random.default_rng(2)
+    L = wl.Layer(spec, None, np.zeros(5, dtype=np.int32), np.zeros(0, dtype=np.int32),
+                 np.zeros(0, dtype=np.float32), rng.random((2, 3, 6, 6), dtype=np.float32),
+                 rng.standard_normal(4).astype(np.float32))
+    dl = DeviceLayer(esc, L)
+    assert (dl.forward(0) == 0).all()
+    got = dl.forward(esc.F_BIAS)
+    assert (got == L.bias[None, :, None, None]).all()
+
+
+# ------------------------------------------------------------------ the paper-shaped layers
+FULL_WHOLE = ["A1b1", "A2b1", "A3b1"]                      # oracle computes every element quickly
+FULL_SAMPLED = ["R56", "R28", "R14", "R7", "R56s2", "G1", "G3", "G5", "A2b64", "S80", "S95",
+                "S80skew", "S80skewperm", "S50"]
+
+
+@pytest.mark.parametrize("name", FULL_WHOLE)
+def test_full_size_layers_whole_output(oracle, name):
+    print("sconv full", name, flush=True)
+    L = wl.make_layer(name)
+    got = DeviceLayer(esc, L).forward(0)
+    ref, bound = oracle_full(oracle, L, 0)
+    assert_within_bound(got, ref, bound, name)
+
+
+@pytest.mark.parametrize("name", FULL_SAMPLED)
+def test_full_size_layers_sampled_outputs(oracle, name):
+    """At the bench's sizes the oracle evaluates sampled output elements one by one; padding is
+    checked in full (bit-exact) and the output must hold no unwritten element."""
+    print("sconv full sampled", name, flush=True)
+    L = wl.make_layer(name)
+    s = L.spec
+    dl = DeviceLayer(esc, L)
+    got = dl.forward(esc.F_BIAS | esc.F_RELU)
+    assert np.isfinite(got).all()
+    pad_ref = oracle.pad_input(L.input, s.pad)
+    assert dl.d_padded.cpu().numpy().tobytes() == pad_ref.tobytes()
+    pts = sample_points(s, 4000, seed=s.seed)
+    Wd = oracle.csr_to_dense(s.M, s.C, s.R, s.S, L.rowptr, L.colidx, L.value)
+    ref, bound = oracle.conv_points(L.input, Wd, pts, s.stride, s.pad, bias=L.bias,
+                                    flags=esc.F_BIAS | esc.F_RELU)
+    g = got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
+    assert_within_bound(g, ref, bound, name)
+    # whole-output property that holds at any size: an all-ones input turns every interior
+    # output into the CSR row sum
+    import torch
+    dl.d_in.fill_(1.0)
+    got1 = dl.forward(0)
+    rowsum = np.array([L.value[a:b].astype(np.float64).sum() for a, b in zip(L.rowptr[:-1], L.rowptr[1:])])
+    rowabs = np.array([np.abs(L.value[a:b]).astype(np.float64).sum() for a, b in zip(L.rowptr[:-1], L.rowptr[1:])])
+    k = -(-s.pad // s.stride)                              # outputs whose window touches the frame
+    inner = got1[:, :, k:s.E - k, k:s.F - k] if k else got1
+    err = np.abs(inner - rowsum[None, :, None, None])
+    assert (err <= 1e-4 * rowabs[None, :, None, None] + 1e-30).all(), name
