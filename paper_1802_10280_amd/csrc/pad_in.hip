@@ -34,7 +34,6 @@ extern "C" int escoin_pad_in(const escoin_conv_desc* desc, const float* d_in, fl
     if (planes >= INT32_MAX) return ESCOIN_ERANGE;
     const int plane = d.Hp * d.Wp;
     dim3 grid((plane + 255) / 256, (unsigned)(planes < 32768 ? planes : 32768));
-    hipLaunchKernelGGL(pad_in_kernel, grid, dim3(256), 0, (hipStream_t)hip_stream, d_in, d_padded,
-                       (int)planes, d.H, d.W, d.Hp, d.Wp, d.pad);
-    return escoin::hip_status(hipGetLastError());
+    return escoin::launch(pad_in_kernel, grid, dim3(256), 0, (hipStream_t)hip_stream, d_in, d_padded,
+                          (int)planes, d.H, d.W, d.Hp, d.Wp, d.pad);
 }

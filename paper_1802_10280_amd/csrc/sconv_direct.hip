@@ -64,10 +64,9 @@ int launch_sconv_direct(const Dims& d, const int32_t* d_rowptr, const int32_t* d
     // indices fit int32 here, but reject rather than fold silently
     if (d.M > 65535 || d.N > 65535) return ESCOIN_ERANGE;
     dim3 grid((EF + per_block - 1) / per_block, d.M, d.N);
-    hipLaunchKernelGGL(sconv_direct_kernel, grid, dim3(kThreads), 0, stream, d_rowptr, d_colidx,
-                       d_value, d_padded, d_out, d_bias, flags, d.M, d.E, d.F, d.Wp, d.stride,
-                       d.C * d.Hp * d.Wp);
-    return hip_status(hipGetLastError());
+    return launch(sconv_direct_kernel, grid, dim3(kThreads), 0, stream, d_rowptr, d_colidx, d_value,
+                  d_padded, d_out, d_bias, flags, d.M, d.E, d.F, d.Wp, d.stride,
+                  d.C * d.Hp * d.Wp);
 }
 
 }  // namespace escoin

@@ -1,0 +1,60 @@
+"""Per-layer driver used by the bench, the smoke check and the tests: packs the CSR once,
+uploads it, owns the torch device buffers and issues the library calls of one forward pass.
+It only marshals arguments; every step of the path runs inside libescoin.so."""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding as B
+
+
+class LayerRunner:
+    def __init__(self, layer, path: str = "auto", flags: int = 0, stream=None):
+        import torch
+        self.layer, self.flags, self.stream = layer, flags, stream
+        s = layer.spec
+        self.desc = B.desc_of(s)
+        self.stretched = B.escoin_sconv_pack(self.desc, layer.rowptr, layer.colidx)
+        dev = "cuda"
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        nz = layer.nnz > 0
+        self.d_rowptr = up(layer.rowptr)
+        self.d_colidx = up(self.stretched) if nz else torch.zeros(1, dtype=torch.int32, device=dev)
+        self.d_value = up(layer.value) if nz else torch.zeros(1, dtype=torch.float32, device=dev)
+        self.d_bias = up(layer.bias) if layer.bias is not None else None
+        self.d_in = up(layer.input)
+        self.d_padded = torch.empty(B.escoin_padded_elems(self.desc), dtype=torch.float32, device=dev)
+        self.d_out = torch.empty((s.N, s.M, s.E, s.F), dtype=torch.float32, device=dev)
+        self.path = "direct" if path == "auto" else path
+        if self.path != "direct":
+            raise ValueError(f"unknown sconv path {path!r}")
+
+    @staticmethod
+    def available_paths(layer):
+        return ["direct"]
+
+    # -- one forward pass ---------------------------------------------------------------
+    def pad_in(self):
+        B.escoin_pad_in(self.desc, self.d_in, self.d_padded, self.stream)
+
+    def sconv(self):
+        B.escoin_sconv_forward(self.desc, self.d_rowptr, self.d_colidx, self.d_value,
+                               self.d_padded, self.d_out, self.d_bias, self.flags, self.stream)
+
+    def kernels(self):
+        return [self.pad_in, self.sconv]
+
+    def kernel_names(self):
+        return ["pad_in", "sconv"]
+
+    def sconv_kernel_name(self):
+        return "sconv_direct_kernel"
+
+    def run(self):
+        for k in self.kernels():
+            k()
+        return self.d_out
+
+    def measured_traffic(self):
+        """HBM bytes per launch from rocprofv3 counters, when a profile has been recorded."""
+        return None
