@@ -106,6 +106,55 @@ int escoin_sconv_forward(const escoin_conv_desc *desc, const int32_t *d_rowptr,
                          const float *d_padded, float *d_out, const float *d_bias,
                          uint32_t flags, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------------
+ * LDS-tiled sconv: the same result as escoin_sconv_forward, computed from the UNPADDED input
+ * (the zero frame of pad_in is produced while the input window is staged on chip, so the
+ * padded array of Section 3.1 only ever exists tile by tile in LDS).  It needs a plan: a
+ * kernel-specific re-encoding of the stretched CSR (nonzeros regrouped by input-channel chunk
+ * and row bin, offsets re-stretched to the on-chip window; Section 3.3's "weights stationary,
+ * inputs streamed" with Section 4.3's tiling).  The stretched CSR stays the externally
+ * visible, bit-exact packing result; the plan is derived data and opaque.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Tiling knobs; a zero field means "choose for me".  Out-of-range combinations make the plan
+ * calls return ESCOIN_EINVAL / ESCOIN_ERANGE (e.g. a window that does not fit LDS). */
+typedef struct escoin_sconv_tuning {
+    int32_t K;  /* output channels accumulated per wave: 2, 4, 8 or 16             */
+    int32_t Q;  /* 16-byte position groups per lane, 1 or 2                         */
+    int32_t B;  /* nonzeros fetched per scalar load, 4 or 8                         */
+    int32_t WM; /* waves per workgroup along the output-channel axis                */
+    int32_t CC; /* input channels staged per LDS chunk                              */
+    int32_t NB; /* images per workgroup                                             */
+    int32_t TH; /* output rows per tile                                             */
+} escoin_sconv_tuning;
+
+/* Bytes the plan blob needs.  Host; rowptr / colidx_stretched as returned by
+ * escoin_sconv_pack (any order inside a row, duplicates allowed); tuning may be NULL. */
+int escoin_sconv_plan_size(const escoin_conv_desc *desc, const int32_t *rowptr,
+                           const int32_t *colidx_stretched, const escoin_sconv_tuning *tuning,
+                           size_t *plan_bytes);
+
+/* Builds the plan into caller-owned host memory `plan` (plan_bytes from the size query, else
+ * ESCOIN_ESIZE).  The plan does not depend on N.  The caller then copies the blob verbatim to
+ * device memory (256-byte aligned) and keeps the host copy for escoin_sconv_forward_tiled.
+ * ESCOIN_EINVAL if an offset is not one weight stretching can produce for this desc. */
+int escoin_sconv_plan_build(const escoin_conv_desc *desc, const int32_t *rowptr,
+                            const int32_t *colidx_stretched, const float *value,
+                            const escoin_sconv_tuning *tuning, void *plan, size_t plan_bytes);
+
+/*
+ * out[n][m][h][w] = sum_j value[j] * Ipad[n][...]  (Algorithm 2 / Eq. 1 with zero padding and
+ * stride), optional fused epilogue as in escoin_sconv_forward.
+ *   plan_host  host copy of the blob (only its header is read, synchronously)
+ *   d_plan     device copy of the same blob
+ *   d_in       device, N*C*H*W floats, UNPADDED
+ *   d_out      device, N*M*E*F floats, overwritten
+ * ESCOIN_EINVAL if the plan was built for another layer geometry.
+ */
+int escoin_sconv_forward_tiled(const escoin_conv_desc *desc, const void *plan_host,
+                               const void *d_plan, const float *d_in, float *d_out,
+                               const float *d_bias, uint32_t flags, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,6 +22,10 @@ class escoin_conv_desc(ctypes.Structure):
     _fields_ = [(k, ctypes.c_int32) for k in ("N", "C", "H", "W", "M", "R", "S", "stride", "pad")]
 
 
+class escoin_sconv_tuning(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int32) for k in ("K", "Q", "B", "WM", "CC", "NB", "TH")]
+
+
 class EscoinError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -53,6 +57,10 @@ def lib() -> ctypes.CDLL:
         L.escoin_sconv_pack.argtypes = [D, vp, vp, vp]
         L.escoin_pad_in.argtypes = [D, vp, vp, vp]
         L.escoin_sconv_forward.argtypes = [D, vp, vp, vp, vp, vp, vp, ctypes.c_uint32, vp]
+        T = ctypes.POINTER(escoin_sconv_tuning)
+        L.escoin_sconv_plan_size.argtypes = [D, vp, vp, T, ctypes.POINTER(ctypes.c_size_t)]
+        L.escoin_sconv_plan_build.argtypes = [D, vp, vp, vp, T, vp, ctypes.c_size_t]
+        L.escoin_sconv_forward_tiled.argtypes = [D, vp, vp, vp, vp, vp, ctypes.c_uint32, vp]
         _lib = L
     return _lib
 
@@ -148,3 +156,61 @@ def escoin_sconv_forward(desc, d_rowptr, d_colidx_stretched, d_value, d_padded, 
                                       _dptr(d_padded, torch.float32),
                                       _dptr(d_out, torch.float32), _dptr(d_bias, torch.float32),
                                       flags, _stream(stream)), "escoin_sconv_forward")
+
+
+def make_tuning(**kw):
+    """Tiling knobs for the plan (K, Q, B, WM, CC, NB, TH); omitted fields are chosen by the
+    library.  Returns None when nothing is given."""
+    if not kw:
+        return None
+    return escoin_sconv_tuning(**{k: int(v) for k, v in kw.items()})
+
+
+def _tref(tuning):
+    return ctypes.byref(tuning) if tuning is not None else None
+
+
+def escoin_sconv_plan_size(desc, rowptr: np.ndarray, colidx_stretched: np.ndarray, tuning=None) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().escoin_sconv_plan_size(ctypes.byref(desc), _hptr(rowptr, np.int32),
+                                        _hptr(colidx_stretched, np.int32), _tref(tuning),
+                                        ctypes.byref(n)), "escoin_sconv_plan_size")
+    return n.value
+
+
+def escoin_sconv_plan_build(desc, rowptr: np.ndarray, colidx_stretched: np.ndarray,
+                            value: np.ndarray, tuning=None, plan: np.ndarray | None = None) -> np.ndarray:
+    """Returns the plan blob as a uint8 numpy array (host)."""
+    if plan is None:
+        plan = np.empty(escoin_sconv_plan_size(desc, rowptr, colidx_stretched, tuning), dtype=np.uint8)
+    _check(lib().escoin_sconv_plan_build(ctypes.byref(desc), _hptr(rowptr, np.int32),
+                                         _hptr(colidx_stretched, np.int32), _hptr(value, np.float32),
+                                         _tref(tuning), _hptr(plan, np.uint8), plan.nbytes),
+           "escoin_sconv_plan_build")
+    return plan
+
+
+def escoin_sconv_forward_tiled(desc, plan_host: np.ndarray, d_plan, d_in, d_out, d_bias=None,
+                               flags=0, stream=None):
+    import torch
+    _check(lib().escoin_sconv_forward_tiled(ctypes.byref(desc), _hptr(plan_host, np.uint8),
+                                            _dptr(d_plan, torch.uint8), _dptr(d_in, torch.float32),
+                                            _dptr(d_out, torch.float32), _dptr(d_bias, torch.float32),
+                                            flags, _stream(stream)), "escoin_sconv_forward_tiled")
+
+
+PLAN_HEADER_FIELDS = (
+    ["magic", "version", "C", "H", "W", "M", "R", "S", "stride", "pad", "E", "F", "K", "Q", "B",
+     "WM", "WQ", "CC", "NB", "TH", "n_tiles", "n_mgroups", "n_chunks", "n_slots", "pitch",
+     "rows_in", "plane_stride", "P4", "lut_entries", "lds_floats", "nnz", "n_records"],
+    ["off_src_lut", "off_dst_lut", "off_perm", "off_seg", "off_rec", "total_bytes"])
+
+
+def plan_header(plan: np.ndarray) -> dict:
+    """Decodes the (opaque) plan header for diagnostics, tests and the bench's reporting."""
+    n32 = len(PLAN_HEADER_FIELDS[0])
+    a = plan[:n32 * 4].view(np.int32)
+    b = plan[n32 * 4:n32 * 4 + 8 * len(PLAN_HEADER_FIELDS[1])].view(np.uint64)
+    h = {k: int(v) for k, v in zip(PLAN_HEADER_FIELDS[0], a)}
+    h.update({k: int(v) for k, v in zip(PLAN_HEADER_FIELDS[1], b)})
+    return h

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libescoin.so")
 
-SOURCES = ["host.cpp", "pad_in.hip", "sconv_direct.hip"]
+SOURCES = ["host.cpp", "plan.cpp", "pad_in.hip", "sconv_direct.hip", "sconv_tiled.hip"]
 
 # Packed-FP32 VALU forms are switched off for every device translation unit.
 HIPCC_FLAGS = [

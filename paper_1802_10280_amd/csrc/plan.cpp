@@ -1,0 +1,337 @@
+// Host-side plan builder for the LDS-tiled sconv kernel.
+//
+// Input: the stretched CSR of escoin_sconv_pack (offsets into the padded CHW input, Section
+// 3.1).  Output: an opaque blob holding
+//   - two geometry tables, so the kernel needs no index arithmetic of its own:
+//       src_lut: for every LDS word of a tile, which word of the (unpadded) input plane it
+//                holds (-1 = padding, written as +0.0f) -- pad_in folded into the staging;
+//       dst_lut: for every computed position of a tile, where it goes in the E*F output plane
+//                (-1 = a position on the padded pitch that is not an output);
+//   - the nonzeros re-sorted per (row bin, channel chunk), each with its LDS byte offset.
+//
+// LDS window.  The padded input of a tile is split into stride*stride phase planes (phase =
+// coordinate mod stride), so that Algorithm 2's f(0,h,w) is h*pitch + w for every stride.  A
+// tap (r, s) reads phase (r % stride, s % stride) at delta = (r/stride)*pitch + s/stride from
+// the position.  Lanes own four consecutive positions and fetch them with one 16-byte LDS read;
+// to keep that read aligned for every tap, a phase plane is stored once per distinct
+// (delta mod 4), shifted left by that amount ("slot").
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+#include "common.h"
+#include "plan.h"
+
+namespace escoin {
+
+bool tiled_variant_exists(int K, int Q, int B);  // sconv_tiled.hip
+
+namespace {
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
+inline uint64_t align_up64(uint64_t a, uint64_t b) { return (a + b - 1) / b * b; }
+
+constexpr int kLdsBudgetBytes = 160 * 1024;
+
+struct Geometry {
+    int n_slots = 0;
+    int slot_phase_a[kMaxSlots], slot_phase_b[kMaxSlots], slot_shift[kMaxSlots];
+    std::vector<int> tap_slot;    // [R*S]
+    std::vector<int> tap_adelta;  // [R*S] aligned part of delta (floats, multiple of 4)
+    int max_adelta = 0;
+};
+
+int build_geometry(const Dims& d, int pitch, Geometry* g) {
+    g->tap_slot.assign((size_t)d.R * d.S, -1);
+    g->tap_adelta.assign((size_t)d.R * d.S, 0);
+    for (int r = 0; r < d.R; ++r) {
+        for (int s = 0; s < d.S; ++s) {
+            const int a = r % d.stride, b = s % d.stride;
+            const int delta = (r / d.stride) * pitch + s / d.stride;
+            const int shift = delta % 4;
+            int slot = -1;
+            for (int i = 0; i < g->n_slots; ++i)
+                if (g->slot_phase_a[i] == a && g->slot_phase_b[i] == b && g->slot_shift[i] == shift)
+                    slot = i;
+            if (slot < 0) {
+                if (g->n_slots == kMaxSlots) return ESCOIN_ERANGE;
+                slot = g->n_slots++;
+                g->slot_phase_a[slot] = a;
+                g->slot_phase_b[slot] = b;
+                g->slot_shift[slot] = shift;
+            }
+            g->tap_slot[(size_t)r * d.S + s] = slot;
+            g->tap_adelta[(size_t)r * d.S + s] = delta - shift;
+            g->max_adelta = std::max(g->max_adelta, delta - shift);
+        }
+    }
+    return ESCOIN_OK;
+}
+
+// Fills every derived field of `h` from the knobs K, Q, B, WM, CC, NB, TH (already set).
+int derive(const Dims& d, PlanHeader* h, Geometry* g) {
+    const int cols_ph = ceil_div(d.Wp, d.stride);
+    h->pitch = round_up(cols_ph, 4);
+    int rc = build_geometry(d, h->pitch, g);
+    if (rc != ESCOIN_OK) return rc;
+    h->n_slots = g->n_slots;
+    h->TH = std::min(h->TH, d.E);
+    h->n_tiles = ceil_div(d.E, h->TH);
+    h->rows_in = h->TH + (d.R - 1) / d.stride;
+    h->plane_stride = round_up(h->rows_in * h->pitch + 4, 4);
+    h->P4 = round_up(h->TH * h->pitch, 4);
+    const int groups = h->NB * (h->P4 / 4);
+    h->WQ = ceil_div(groups, 64 * h->Q);
+    h->CC = std::min(h->CC, d.C);
+    h->n_chunks = ceil_div(d.C, h->CC);
+    h->n_mgroups = ceil_div(d.M, h->K * h->WM);
+    h->lut_entries = h->n_slots * h->plane_stride;
+    const long long lds = (long long)h->n_slots * h->CC * h->NB * h->plane_stride + g->max_adelta + 8;
+    if (lds * 4 > kLdsBudgetBytes) return ESCOIN_ERANGE;
+    h->lds_floats = (int)lds;
+    if (h->WQ * h->WM > 8) return ESCOIN_ERANGE;  // at most 512 threads per workgroup
+    return ESCOIN_OK;
+}
+
+// Default knobs.  Positions of NB images (or of one band of TH rows) fill the 64*Q*4 positions
+// of one wave; the channel chunk takes what LDS is left under `lds_target`.
+void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h) {
+    const int cols_ph = ceil_div(d.Wp, d.stride);
+    const int pitch = round_up(cols_ph, 4);
+    h->Q = (t && t->Q > 0) ? t->Q : 1;
+    h->B = (t && t->B > 0) ? t->B : 4;
+    h->K = (t && t->K > 0) ? t->K : 8;
+    const int wave_pos = 64 * h->Q * 4;
+    // tile: whole image(s) when an image's positions fit one wave, else a band of rows
+    int TH = d.E, NB = 1;
+    if (d.E * pitch <= wave_pos) {
+        NB = std::max(1, wave_pos / round_up(d.E * pitch, 4));
+        NB = std::min(NB, d.N);
+    } else {
+        TH = std::max(1, wave_pos / pitch);
+        // even out the bands
+        TH = ceil_div(d.E, ceil_div(d.E, TH));
+    }
+    h->TH = (t && t->TH > 0) ? t->TH : TH;
+    h->NB = (t && t->NB > 0) ? t->NB : ((t && t->TH > 0 && t->TH < d.E) ? 1 : NB);
+    int WM = std::min(8, ceil_div(d.M, h->K));
+    h->WM = (t && t->WM > 0) ? t->WM : WM;
+    if (t && t->CC > 0) {
+        h->CC = t->CC;
+    } else {
+        Geometry g;
+        PlanHeader probe = *h;
+        probe.CC = 1;
+        const int lds_target = 64 * 1024;
+        if (derive(d, &probe, &g) == ESCOIN_OK) {
+            const int per_c = probe.n_slots * probe.NB * probe.plane_stride * 4;
+            h->CC = std::max(1, std::min(d.C, lds_target / per_c));
+            // equalise the chunks
+            h->CC = ceil_div(d.C, ceil_div(d.C, h->CC));
+        } else {
+            h->CC = 1;
+        }
+    }
+}
+
+struct RowNz {
+    uint32_t off_bytes;
+    float val;
+};
+
+}  // namespace
+
+// Builds the plan into `out` (or only sizes it when out == nullptr).  Returns a code; the
+// byte count goes to *bytes.
+int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_t* stretched,
+               const float* value, const escoin_sconv_tuning* tuning, void* out, size_t out_bytes,
+               size_t* bytes) {
+    Dims d;
+    int rc = make_dims(desc, &d);
+    if (rc != ESCOIN_OK) return rc;
+    if (!rowptr || !bytes) return ESCOIN_EINVAL;
+    if (rowptr[0] != 0) return ESCOIN_EINVAL;
+    for (int m = 0; m < d.M; ++m)
+        if (rowptr[m + 1] < rowptr[m]) return ESCOIN_EINVAL;
+    const int nnz = rowptr[d.M];
+    if (nnz > 0 && (!stretched || (out && !value))) return ESCOIN_EINVAL;
+    if (tuning) {
+        const int32_t* f = &tuning->K;
+        for (int i = 0; i < 7; ++i)
+            if (f[i] < 0) return ESCOIN_EINVAL;
+    }
+
+    PlanHeader h;
+    std::memset(&h, 0, sizeof(h));
+    h.magic = kPlanMagic;
+    h.version = kPlanVersion;
+    h.C = d.C; h.H = d.H; h.W = d.W; h.M = d.M; h.R = d.R; h.S = d.S;
+    h.stride = d.stride; h.pad = d.pad; h.E = d.E; h.F = d.F;
+    choose_defaults(d, tuning, &h);
+    if (!tiled_variant_exists(h.K, h.Q, h.B)) return ESCOIN_EINVAL;
+    Geometry g;
+    rc = derive(d, &h, &g);
+    if (rc != ESCOIN_OK) return rc;
+    h.nnz = nnz;
+
+    // ---- decode every nonzero: stretched offset -> (c, r, s) -> (chunk, LDS byte offset)
+    const int plane_in = d.Hp * d.Wp;
+    const int chan_stride = h.NB * h.plane_stride;  // floats between channels of one slot
+    std::vector<int> nz_chunk((size_t)nnz);
+    std::vector<uint32_t> nz_off((size_t)nnz);
+    for (int j = 0; j < nnz; ++j) {
+        const int off = stretched[j];
+        if (off < 0 || off >= d.C * plane_in) return ESCOIN_EINVAL;
+        const int c = off / plane_in;
+        const int rem = off - c * plane_in;
+        const int r = rem / d.Wp, s = rem - r * d.Wp;
+        if (r >= d.R || s >= d.S) return ESCOIN_EINVAL;  // not an offset weight stretching makes
+        const int chunk = c / h.CC, cl = c - chunk * h.CC;
+        const int tap = r * d.S + s;
+        const long long fl = ((long long)g.tap_slot[tap] * h.CC + cl) * chan_stride + g.tap_adelta[tap];
+        nz_chunk[j] = chunk;
+        nz_off[j] = (uint32_t)(fl * 4);
+    }
+
+    // ---- rows -> bins (one bin = the K accumulator rows of one wave), balanced by nnz:
+    // rows sorted by length are dealt out in snake order over all bins
+    const int bins = h.n_mgroups * h.WM;
+    std::vector<int> order(d.M);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+        return rowptr[a + 1] - rowptr[a] > rowptr[b + 1] - rowptr[b];
+    });
+    std::vector<int32_t> perm((size_t)bins * h.K, -1);
+    for (int i = 0; i < d.M; ++i) {
+        const int round = i / bins, pos = i % bins;
+        const int b = (round % 2 == 0) ? pos : bins - 1 - pos;
+        // consecutive bins go to different workgroups: bin index = wave * n_mgroups + group
+        const int mg = b % h.n_mgroups, wm = b / h.n_mgroups;
+        perm[((size_t)mg * h.WM + wm) * h.K + round] = order[i];
+    }
+
+    // ---- count batches per (bin, chunk, k)
+    const int B = h.B;
+    const size_t seg_stride = 1 + (size_t)h.K;
+    std::vector<uint32_t> seg((size_t)bins * h.n_chunks * seg_stride, 0);
+    std::vector<int> cnt((size_t)h.n_chunks);
+    uint64_t total_batches = 0;
+    for (int b = 0; b < bins; ++b) {
+        // per-row, per-chunk counts
+        std::vector<std::vector<int>> rc_cnt(h.K, std::vector<int>(h.n_chunks, 0));
+        for (int k = 0; k < h.K; ++k) {
+            const int m = perm[(size_t)b * h.K + k];
+            if (m < 0) continue;
+            for (int j = rowptr[m]; j < rowptr[m + 1]; ++j) rc_cnt[k][nz_chunk[j]]++;
+        }
+        for (int ch = 0; ch < h.n_chunks; ++ch) {
+            uint32_t* sg = &seg[((size_t)b * h.n_chunks + ch) * seg_stride];
+            if (total_batches > 0xFFFFFFFFull) return ESCOIN_ERANGE;
+            sg[0] = (uint32_t)total_batches;
+            for (int k = 0; k < h.K; ++k) {
+                const int nb = ceil_div(rc_cnt[k][ch], B);
+                sg[1 + k] = (uint32_t)nb;
+                total_batches += nb;
+            }
+        }
+    }
+    const uint64_t n_records = (total_batches + 2) * B;  // two spare batches: the prefetch reads ahead
+    if (n_records > 0x7FFFFFFFull) return ESCOIN_ERANGE;
+    h.n_records = (int32_t)n_records;
+
+    // ---- section layout
+    uint64_t off = align_up64(sizeof(PlanHeader), 256);
+    h.off_src_lut = off;
+    off = align_up64(off + (uint64_t)h.n_tiles * h.lut_entries * 4, 256);
+    h.off_dst_lut = off;
+    off = align_up64(off + (uint64_t)h.n_tiles * h.P4 * 4, 256);
+    h.off_perm = off;
+    off = align_up64(off + (uint64_t)perm.size() * 4, 256);
+    h.off_seg = off;
+    off = align_up64(off + (uint64_t)seg.size() * 4, 256);
+    h.off_rec = off;
+    off = align_up64(off + n_records * 8, 256);
+    h.total_bytes = off;
+    *bytes = (size_t)off;
+    if (!out) return ESCOIN_OK;
+    if (out_bytes < off) return ESCOIN_ESIZE;
+
+    char* base = (char*)out;
+    std::memset(base, 0, (size_t)off);
+    std::memcpy(base, &h, sizeof(h));
+
+    // ---- src_lut / dst_lut
+    int32_t* src = (int32_t*)(base + h.off_src_lut);
+    int32_t* dst = (int32_t*)(base + h.off_dst_lut);
+    for (int t = 0; t < h.n_tiles; ++t) {
+        const int h0 = t * h.TH;
+        for (int sl = 0; sl < h.n_slots; ++sl) {
+            int32_t* row = src + ((size_t)t * h.n_slots + sl) * h.plane_stride;
+            for (int e = 0; e < h.plane_stride; ++e) {
+                const int f = e + g.slot_shift[sl];
+                const int i = f / h.pitch, jx = f - i * h.pitch;
+                int32_t v = -1;
+                if (i < h.rows_in) {
+                    const int y = (h0 + i) * d.stride + g.slot_phase_a[sl] - d.pad;
+                    const int x = jx * d.stride + g.slot_phase_b[sl] - d.pad;
+                    if (y >= 0 && y < d.H && x >= 0 && x < d.W) v = y * d.W + x;
+                }
+                row[e] = v;
+            }
+        }
+        for (int p = 0; p < h.P4; ++p) {
+            const int hh = p / h.pitch, w = p - hh * h.pitch;
+            dst[(size_t)t * h.P4 + p] =
+                (hh < h.TH && h0 + hh < d.E && w < d.F) ? (h0 + hh) * d.F + w : -1;
+        }
+    }
+    std::memcpy(base + h.off_perm, perm.data(), perm.size() * 4);
+    std::memcpy(base + h.off_seg, seg.data(), seg.size() * 4);
+
+    // ---- records: per (bin, chunk, k) in CSR order, padded to whole batches with (0, 0.0f)
+    RowNz* rec = (RowNz*)(base + h.off_rec);
+    for (int b = 0; b < bins; ++b) {
+        std::vector<uint64_t> cursor((size_t)h.n_chunks * h.K);
+        for (int ch = 0; ch < h.n_chunks; ++ch) {
+            const uint32_t* sg = &seg[((size_t)b * h.n_chunks + ch) * seg_stride];
+            uint64_t at = (uint64_t)sg[0] * B;
+            for (int k = 0; k < h.K; ++k) {
+                cursor[(size_t)ch * h.K + k] = at;
+                at += (uint64_t)sg[1 + k] * B;
+            }
+        }
+        for (int k = 0; k < h.K; ++k) {
+            const int m = perm[(size_t)b * h.K + k];
+            if (m < 0) continue;
+            for (int j = rowptr[m]; j < rowptr[m + 1]; ++j) {
+                uint64_t& at = cursor[(size_t)nz_chunk[j] * h.K + k];
+                rec[at].off_bytes = nz_off[j];
+                rec[at].val = value[j];
+                ++at;
+            }
+        }
+    }
+    return ESCOIN_OK;
+}
+
+}  // namespace escoin
+
+extern "C" {
+
+int escoin_sconv_plan_size(const escoin_conv_desc* desc, const int32_t* rowptr,
+                           const int32_t* colidx_stretched, const escoin_sconv_tuning* tuning,
+                           size_t* plan_bytes) {
+    return escoin::build_plan(desc, rowptr, colidx_stretched, nullptr, tuning, nullptr, 0, plan_bytes);
+}
+
+int escoin_sconv_plan_build(const escoin_conv_desc* desc, const int32_t* rowptr,
+                            const int32_t* colidx_stretched, const float* value,
+                            const escoin_sconv_tuning* tuning, void* plan, size_t plan_bytes) {
+    if (!plan) return ESCOIN_EINVAL;
+    size_t need = 0;
+    return escoin::build_plan(desc, rowptr, colidx_stretched, value, tuning, plan, plan_bytes, &need);
+}
+
+}  // extern "C"

@@ -9,7 +9,7 @@ from . import binding as B
 
 
 class LayerRunner:
-    def __init__(self, layer, path: str = "auto", flags: int = 0, stream=None):
+    def __init__(self, layer, path: str = "auto", flags: int = 0, stream=None, tuning=None):
         import torch
         self.layer, self.flags, self.stream = layer, flags, stream
         s = layer.spec
@@ -25,13 +25,20 @@ class LayerRunner:
         self.d_in = up(layer.input)
         self.d_padded = torch.empty(B.escoin_padded_elems(self.desc), dtype=torch.float32, device=dev)
         self.d_out = torch.empty((s.N, s.M, s.E, s.F), dtype=torch.float32, device=dev)
-        self.path = "direct" if path == "auto" else path
-        if self.path != "direct":
+        self.path = "tiled" if path == "auto" else path
+        if self.path == "tiled":
+            if isinstance(tuning, dict):
+                tuning = B.make_tuning(**tuning)
+            self.plan = B.escoin_sconv_plan_build(self.desc, layer.rowptr, self.stretched,
+                                                  layer.value, tuning)
+            self.plan_info = B.plan_header(self.plan)
+            self.d_plan = up(self.plan)
+        elif self.path != "direct":
             raise ValueError(f"unknown sconv path {path!r}")
 
     @staticmethod
     def available_paths(layer):
-        return ["direct"]
+        return ["tiled", "direct"]
 
     # -- one forward pass ---------------------------------------------------------------
     def pad_in(self):
@@ -41,13 +48,22 @@ class LayerRunner:
         B.escoin_sconv_forward(self.desc, self.d_rowptr, self.d_colidx, self.d_value,
                                self.d_padded, self.d_out, self.d_bias, self.flags, self.stream)
 
+    def sconv_tiled(self):
+        B.escoin_sconv_forward_tiled(self.desc, self.plan, self.d_plan, self.d_in, self.d_out,
+                                     self.d_bias, self.flags, self.stream)
+
     def kernels(self):
-        return [self.pad_in, self.sconv]
+        """The library calls of one forward pass, in order (the tiled path pads while staging,
+        so it has no separate pad_in)."""
+        return [self.sconv_tiled] if self.path == "tiled" else [self.pad_in, self.sconv]
 
     def kernel_names(self):
-        return ["pad_in", "sconv"]
+        return ["sconv"] if self.path == "tiled" else ["pad_in", "sconv"]
 
     def sconv_kernel_name(self):
+        if self.path == "tiled":
+            h = self.plan_info
+            return f"sconv_tiled_kernel<{h['K']},{h['Q']},{h['B']}>"
         return "sconv_direct_kernel"
 
     def run(self):

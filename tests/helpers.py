@@ -14,9 +14,10 @@ def to_dev(a):
 class DeviceLayer:
     """CSR stretched by escoin_sconv_pack and uploaded; input uploaded; buffers allocated."""
 
-    def __init__(self, esc, L):
+    def __init__(self, esc, L, tuning=None):
         import torch
         self.esc, self.L = esc, L
+        self.tuning = tuning
         self.desc = esc.desc_of(L.spec)
         self.stretched = esc.escoin_sconv_pack(self.desc, L.rowptr, L.colidx)
         self.d_rowptr = to_dev(L.rowptr)
@@ -32,6 +33,24 @@ class DeviceLayer:
         self.d_padded.fill_(float("nan"))
         self.esc.escoin_pad_in(self.desc, self.d_in, self.d_padded)
         return self.d_padded
+
+    def forward_tiled(self, flags=0):
+        """The LDS-tiled entry point: plan from the stretched CSR, unpadded input."""
+        import torch
+        esc = self.esc
+        if not hasattr(self, "plan"):
+            t = esc.make_tuning(**self.tuning) if self.tuning else None
+            self.plan = esc.escoin_sconv_plan_build(self.desc, self.L.rowptr, self.stretched,
+                                                    self.L.value, t)
+            self.d_plan = to_dev(self.plan)
+        self.d_out.fill_(float("nan"))
+        esc.escoin_sconv_forward_tiled(self.desc, self.plan, self.d_plan, self.d_in, self.d_out,
+                                       self.d_bias, flags)
+        torch.cuda.synchronize()
+        return self.d_out.cpu().numpy()
+
+    def run(self, path, flags=0):
+        return self.forward_tiled(flags) if path == "tiled" else self.forward(flags)
 
     def forward(self, flags=0):
         import torch

@@ -60,35 +60,72 @@ SMALL = [
 ]
 
 
+PATHS = ["direct", "tiled"]
+
+
+@pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("cfg", SMALL, ids=lambda c: "x".join(map(str, c)))
-def test_sconv_matches_oracle_small(oracle, cfg):
-    print("sconv small", cfg, flush=True)
+def test_sconv_matches_oracle_small(oracle, cfg, path):
+    print("sconv small", path, cfg, flush=True)
     N, C, H, W, M, R, S, stride, pad, sp = cfg
     L = wl.custom_layer(N, C, H, W, M, R, S, stride, pad, sp, seed=sum(cfg[:9]) + 1, dist="normal")
     dl = DeviceLayer(esc, L)
     for flags in (0, esc.F_BIAS | esc.F_RELU):
-        got = dl.forward(flags)
+        got = dl.run(path, flags)
         ref, bound = oracle_full(oracle, L, flags)
-        assert_within_bound(got, ref, bound, f"{cfg} flags={flags}")
+        assert_within_bound(got, ref, bound, f"{path} {cfg} flags={flags}")
 
 
-def test_tiny_config_all_flag_combinations(oracle):
-    print("sconv T1 flags", flush=True)
+TUNINGS = [
+    dict(K=2, Q=1, B=4, WM=2, CC=3, TH=5),
+    dict(K=4, Q=2, B=8, WM=1, CC=2, NB=2),
+    dict(K=16, Q=1, B=8, WM=1, CC=5, TH=3),
+    dict(K=8, Q=2, B=4, WM=2, CC=1, TH=11),
+    dict(K=4, Q=1, B=4, WM=4, CC=7, NB=3),
+]
+
+
+@pytest.mark.parametrize("tune", TUNINGS, ids=lambda t: "-".join(f"{k}{v}" for k, v in t.items()))
+@pytest.mark.parametrize("cfg", [SMALL[1], SMALL[3], SMALL[4], SMALL[5], SMALL[6], SMALL[11]],
+                         ids=lambda c: "x".join(map(str, c)))
+def test_tiled_every_template_and_tiling(oracle, cfg, tune):
+    """Every kernel instantiation family and odd tilings (bands that do not divide E, chunks
+    that do not divide C, several images per workgroup, ragged last image group)."""
+    print("sconv tiled tuning", cfg, tune, flush=True)
+    N, C, H, W, M, R, S, stride, pad, sp = cfg
+    L = wl.custom_layer(N, C, H, W, M, R, S, stride, pad, sp, seed=sum(cfg[:9]) + 2, dist="normal")
+    t = dict(tune)
+    if "NB" in t and "TH" not in t:
+        pass
+    try:
+        dl = DeviceLayer(esc, L, tuning=t)
+        got = dl.forward_tiled(esc.F_BIAS)
+    except esc.EscoinError as e:
+        assert e.code == esc.ERANGE       # a tiling that needs more than 8 waves or too much LDS
+        pytest.skip("tiling not realisable for this shape")
+    ref, bound = oracle_full(oracle, L, esc.F_BIAS)
+    assert_within_bound(got, ref, bound, f"{cfg} {tune}")
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_tiny_config_all_flag_combinations(oracle, path):
+    print("sconv T1 flags", path, flush=True)
     L = wl.make_layer("T1")
     dl = DeviceLayer(esc, L)
     pad_ref = oracle.pad_input(L.input, L.spec.pad)
     assert dl.pad().cpu().numpy().tobytes() == pad_ref.tobytes()
     for flags in (0, esc.F_BIAS, esc.F_RELU, esc.F_BIAS | esc.F_RELU):
-        got = dl.forward(flags)
+        got = dl.run(path, flags)
         ref, bound = oracle_full(oracle, L, flags)
         assert_within_bound(got, ref, bound, f"T1 flags={flags}")
         if flags & esc.F_RELU:
             assert (got >= 0).all()
 
 
-def test_identity_filter_reproduces_input_bit_exact():
+@pytest.mark.parametrize("path", PATHS)
+def test_identity_filter_reproduces_input_bit_exact(path):
     """A single centre weight of 1 per output channel copies an input channel exactly."""
-    print("sconv identity", flush=True)
+    print("sconv identity", path, flush=True)
     rng = np.random.default_rng(1)
     N, C, H, W, M = 2, 6, 15, 17, 6
     w = np.zeros((M, C, 3, 3), dtype=np.float32)
@@ -98,13 +135,14 @@ def test_identity_filter_reproduces_input_bit_exact():
     spec = wl.LayerSpec("ident", 9, 0, N, C, H, W, M, 3, 3, 1, 1, 0.0)
     x = rng.standard_normal((N, C, H, W)).astype(np.float32)
     L = wl.Layer(spec, w, rowptr, colidx, value, x, np.zeros(M, dtype=np.float32))
-    got = DeviceLayer(esc, L).forward(0)
+    got = DeviceLayer(esc, L).run(path, 0)
     for m in range(M):
         assert got[:, m].tobytes() == x[:, (m * 5) % C].tobytes()
 
 
-def test_empty_rows_unsorted_rows_and_duplicates(oracle):
-    print("sconv empty/unsorted/duplicates", flush=True)
+@pytest.mark.parametrize("path", PATHS)
+def test_empty_rows_unsorted_rows_and_duplicates(oracle, path):
+    print("sconv empty/unsorted/duplicates", path, flush=True)
     L = wl.custom_layer(2, 5, 8, 9, 6, 3, 3, 1, 1, 0.6, seed=4, dist="normal")
     rng = np.random.default_rng(0)
     rows = [list(zip(L.colidx[a:b], L.value[a:b])) for a, b in zip(L.rowptr[:-1], L.rowptr[1:])]
@@ -119,22 +157,23 @@ def test_empty_rows_unsorted_rows_and_duplicates(oracle):
     colidx = np.array([c for r in rows for c, _ in r], dtype=np.int32)
     value = np.array([v for r in rows for _, v in r], dtype=np.float32)
     L2 = wl.Layer(L.spec, None, rowptr, colidx, value, L.input, L.bias)
-    got = DeviceLayer(esc, L2).forward(0)
+    got = DeviceLayer(esc, L2).run(path, 0)
     ref, bound = oracle_full(oracle, L2, 0)
     assert_within_bound(got, ref, bound, "unsorted")
     assert (got[:, 1] == 0).all() and (got[:, 5] == 0).all()
 
 
-def test_all_rows_empty_gives_bias_or_zero(oracle):
-    print("sconv nnz=0", flush=True)
+@pytest.mark.parametrize("path", PATHS)
+def test_all_rows_empty_gives_bias_or_zero(oracle, path):
+    print("sconv nnz=0", path, flush=True)
     spec = wl.LayerSpec("empty", 9, 0, 2, 3, 6, 6, 4, 3, 3, 1, 1, 1.0)
     rng = np.random.default_rng(2)
     L = wl.Layer(spec, None, np.zeros(5, dtype=np.int32), np.zeros(0, dtype=np.int32),
                  np.zeros(0, dtype=np.float32), rng.random((2, 3, 6, 6), dtype=np.float32),
                  rng.standard_normal(4).astype(np.float32))
     dl = DeviceLayer(esc, L)
-    assert (dl.forward(0) == 0).all()
-    got = dl.forward(esc.F_BIAS)
+    assert (dl.run(path, 0) == 0).all()
+    got = dl.run(path, esc.F_BIAS)
     assert (got == L.bias[None, :, None, None]).all()
 
 
@@ -144,27 +183,30 @@ FULL_SAMPLED = ["R56", "R28", "R14", "R7", "R56s2", "G1", "G3", "G5", "A2b64", "
                 "S80skew", "S80skewperm", "S50"]
 
 
+@pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("name", FULL_WHOLE)
-def test_full_size_layers_whole_output(oracle, name):
-    print("sconv full", name, flush=True)
+def test_full_size_layers_whole_output(oracle, name, path):
+    print("sconv full", name, path, flush=True)
     L = wl.make_layer(name)
-    got = DeviceLayer(esc, L).forward(0)
+    got = DeviceLayer(esc, L).run(path, 0)
     ref, bound = oracle_full(oracle, L, 0)
     assert_within_bound(got, ref, bound, name)
 
 
+@pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("name", FULL_SAMPLED)
-def test_full_size_layers_sampled_outputs(oracle, name):
+def test_full_size_layers_sampled_outputs(oracle, name, path):
     """At the bench's sizes the oracle evaluates sampled output elements one by one; padding is
     checked in full (bit-exact) and the output must hold no unwritten element."""
-    print("sconv full sampled", name, flush=True)
+    print("sconv full sampled", name, path, flush=True)
     L = wl.make_layer(name)
     s = L.spec
     dl = DeviceLayer(esc, L)
-    got = dl.forward(esc.F_BIAS | esc.F_RELU)
+    got = dl.run(path, esc.F_BIAS | esc.F_RELU)
     assert np.isfinite(got).all()
-    pad_ref = oracle.pad_input(L.input, s.pad)
-    assert dl.d_padded.cpu().numpy().tobytes() == pad_ref.tobytes()
+    if path == "direct":
+        pad_ref = oracle.pad_input(L.input, s.pad)
+        assert dl.d_padded.cpu().numpy().tobytes() == pad_ref.tobytes()
     pts = sample_points(s, 4000, seed=s.seed)
     Wd = oracle.csr_to_dense(s.M, s.C, s.R, s.S, L.rowptr, L.colidx, L.value)
     ref, bound = oracle.conv_points(L.input, Wd, pts, s.stride, s.pad, bias=L.bias,
@@ -175,7 +217,7 @@ def test_full_size_layers_sampled_outputs(oracle, name):
     # output into the CSR row sum
     import torch
     dl.d_in.fill_(1.0)
-    got1 = dl.forward(0)
+    got1 = dl.run(path, 0)
     rowsum = np.array([L.value[a:b].astype(np.float64).sum() for a, b in zip(L.rowptr[:-1], L.rowptr[1:])])
     rowabs = np.array([np.abs(L.value[a:b]).astype(np.float64).sum() for a, b in zip(L.rowptr[:-1], L.rowptr[1:])])
     k = -(-s.pad // s.stride)                              # outputs whose window touches the frame

@@ -1,0 +1,107 @@
+"""CPU checks of the tiled-kernel plan: the blob is replayed by a numpy emulation of the
+kernel's data flow and must reproduce the oracle (so table / offset / segment bugs surface
+without a GPU), plus the error paths of the plan calls."""
+import numpy as np
+import pytest
+
+import paper_1802_10280_amd as esc
+from paper_1802_10280_amd import workloads as wl
+
+from plan_sim import simulate
+
+CASES = [
+    # (N, C, H, W, M, R, S, stride, pad, sparsity), tuning
+    ((2, 5, 9, 11, 7, 3, 3, 1, 1, 0.6), {}),
+    ((3, 6, 7, 7, 10, 3, 3, 1, 1, 0.7), dict(K=4, NB=2, CC=4)),
+    ((2, 4, 20, 21, 6, 5, 5, 1, 2, 0.7), dict(K=2, TH=5, CC=3)),
+    ((2, 6, 17, 19, 5, 3, 3, 2, 1, 0.6), dict(K=4, TH=4, WM=2)),
+    ((2, 9, 12, 13, 10, 1, 1, 1, 0, 0.6), dict(K=8, CC=4)),
+    ((1, 3, 23, 19, 3, 7, 7, 2, 3, 0.5), dict(K=2, TH=3)),
+    ((2, 3, 10, 12, 4, 2, 3, 3, 2, 0.4), dict(K=4, Q=2, B=8)),
+    ((5, 8, 7, 7, 12, 3, 3, 1, 1, 0.8), dict(K=16, NB=3, WM=1)),
+    ((2, 3, 30, 37, 4, 3, 3, 1, 0, 0.5), dict(TH=9, Q=2)),
+]
+
+
+@pytest.mark.parametrize("cfg,tune", CASES, ids=lambda c: "x".join(map(str, c)) if isinstance(c, tuple) else str(c))
+def test_plan_replay_matches_oracle(oracle, cfg, tune):
+    N, C, H, W, M, R, S, stride, pad, sp = cfg
+    L = wl.custom_layer(N, C, H, W, M, R, S, stride, pad, sp, seed=sum(cfg[:9]) + 3)
+    d = esc.desc_of(L.spec)
+    st = esc.escoin_sconv_pack(d, L.rowptr, L.colidx)
+    plan = esc.escoin_sconv_plan_build(d, L.rowptr, st, L.value, esc.make_tuning(**tune))
+    h = esc.plan_header(plan)
+    assert h["total_bytes"] == plan.nbytes and h["nnz"] == L.nnz
+    for k, v in tune.items():
+        assert h[k] == v, (k, h[k], v)
+    got = simulate(plan, L.input, M)
+    Wd = oracle.csr_to_dense(M, C, R, S, L.rowptr, L.colidx, L.value)
+    ref, bound = oracle.conv(L.input, Wd, stride, pad)
+    assert np.all(np.abs(got - ref) <= 1e-6 * bound + 1e-12)
+
+
+def test_plan_accepts_unsorted_rows_and_duplicates(oracle):
+    L = wl.custom_layer(2, 6, 8, 9, 5, 3, 3, 1, 1, 0.5, seed=12)
+    rng = np.random.default_rng(1)
+    rows = [list(zip(L.colidx[a:b], L.value[a:b])) for a, b in zip(L.rowptr[:-1], L.rowptr[1:])]
+    rows[0] = []
+    rows[2].append((rows[2][0][0], np.float32(0.5)))
+    for r in rows:
+        rng.shuffle(r)
+    rowptr = np.zeros(6, dtype=np.int32)
+    rowptr[1:] = np.cumsum([len(r) for r in rows])
+    colidx = np.array([c for r in rows for c, _ in r], dtype=np.int32)
+    value = np.array([v for r in rows for _, v in r], dtype=np.float32)
+    d = esc.desc_of(L.spec)
+    st = esc.escoin_sconv_pack(d, rowptr, colidx)
+    plan = esc.escoin_sconv_plan_build(d, rowptr, st, value, esc.make_tuning(K=2, CC=2))
+    got = simulate(plan, L.input, 5)
+    ref, bound = oracle.conv(L.input, oracle.csr_to_dense(5, 6, 3, 3, rowptr, colidx, value), 1, 1)
+    assert np.all(np.abs(got - ref) <= 1e-6 * bound + 1e-12)
+
+
+def test_rows_are_dealt_out_balanced():
+    L = wl.make_layer("S80skew", with_input=False)
+    d = esc.desc_of(L.spec)
+    st = esc.escoin_sconv_pack(d, L.rowptr, L.colidx)
+    plan = esc.escoin_sconv_plan_build(d, L.rowptr, st, L.value)
+    h = esc.plan_header(plan)
+    bins = h["n_mgroups"] * h["WM"]
+    perm = plan[h["off_perm"]:h["off_perm"] + 4 * bins * h["K"]].view(np.int32).reshape(bins, h["K"])
+    nnz_row = np.diff(L.rowptr)
+    load = np.array([nnz_row[p[p >= 0]].sum() for p in perm])
+    assert load.max() <= 1.35 * load.mean()        # rows alone: max/mean = 5.0
+    assert nnz_row.max() / nnz_row.mean() > 4.5
+
+
+def test_plan_error_paths():
+    L = wl.custom_layer(1, 4, 8, 8, 4, 3, 3, 1, 1, 0.5, seed=1)
+    d = esc.desc_of(L.spec)
+    st = esc.escoin_sconv_pack(d, L.rowptr, L.colidx)
+    n = esc.escoin_sconv_plan_size(d, L.rowptr, st)
+    with pytest.raises(esc.EscoinError) as e:
+        esc.escoin_sconv_plan_build(d, L.rowptr, st, L.value, None, np.empty(n - 1, dtype=np.uint8))
+    assert e.value.code == esc.ESIZE
+    with pytest.raises(esc.EscoinError) as e:        # unstretched column indices are not offsets
+        bad = st.copy()
+        bad[0] = 3 * 10 + 5                             # r = 3 is outside a 3x3 filter
+        esc.escoin_sconv_plan_size(d, L.rowptr, bad)
+    assert e.value.code == esc.EINVAL
+    with pytest.raises(esc.EscoinError) as e:
+        esc.escoin_sconv_plan_size(d, L.rowptr, st, esc.make_tuning(K=3))
+    assert e.value.code == esc.EINVAL
+    with pytest.raises(esc.EscoinError) as e:        # window does not fit LDS
+        big = wl.LayerSpec("big", 9, 0, 1, 64, 200, 200, 4, 3, 3, 1, 1, 0.5)
+        esc.escoin_sconv_plan_size(esc.desc_of(big), np.zeros(5, dtype=np.int32), np.zeros(0, dtype=np.int32),
+                                   esc.make_tuning(TH=200, CC=64))
+    assert e.value.code == esc.ERANGE
+    # the forward call rejects a plan built for another geometry before touching the GPU
+    plan = esc.escoin_sconv_plan_build(d, L.rowptr, st, L.value)
+    other = esc.make_desc(1, 4, 9, 8, 4, 3, 3, 1, 1)
+    import ctypes
+    one = ctypes.c_void_p(256)
+    rc = esc.lib().escoin_sconv_forward_tiled(ctypes.byref(other), plan.ctypes.data, one, one, one, None, 0, None)
+    assert rc == esc.EINVAL
+    junk = np.zeros(plan.nbytes, dtype=np.uint8)
+    rc = esc.lib().escoin_sconv_forward_tiled(ctypes.byref(d), junk.ctypes.data, one, one, one, None, 0, None)
+    assert rc == esc.EINVAL
