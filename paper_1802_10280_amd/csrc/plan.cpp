@@ -3,11 +3,14 @@
 // Input: the stretched CSR of escoin_sconv_pack (offsets into the padded CHW input, Section
 // 3.1).  Output: an opaque blob holding
 //   - two geometry tables, so the kernel needs no index arithmetic of its own:
-//       src_lut: for every LDS word of a tile, which word of the (unpadded) input plane it
-//                holds (-1 = padding, written as +0.0f) -- pad_in folded into the staging;
+//       items:   for every input word a tile's window needs, its offset in the (unpadded)
+//                input plane and the LDS words that hold it; words of the zero frame have no
+//                item and stay +0.0f -- pad_in folded into the staging;
 //       dst_lut: for every computed position of a tile, where it goes in the E*F output plane
 //                (-1 = a position on the padded pitch that is not an output);
-//   - the nonzeros re-sorted per (row bin, channel chunk), each with its LDS byte offset.
+//   - the nonzeros re-sorted per (output-channel group, channel chunk, wave, row), each with
+//     its LDS byte offset, so that the records a workgroup needs for one chunk are one
+//     contiguous block it can copy into LDS (Section 3.3 stages colidx/value on chip).
 //
 // LDS window.  The padded input of a tile is split into stride*stride phase planes (phase =
 // coordinate mod stride), so that Algorithm 2's f(0,h,w) is h*pitch + w for every stride.  A
@@ -15,6 +18,8 @@
 // the position.  Lanes own four consecutive positions and fetch them with one 16-byte LDS read;
 // to keep that read aligned for every tap, a phase plane is stored once per distinct
 // (delta mod 4), shifted left by that amount ("slot").
+#include <limits.h>
+
 #include <algorithm>
 #include <cstring>
 #include <numeric>
@@ -87,10 +92,13 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
     h->CC = std::min(h->CC, d.C);
     h->n_chunks = ceil_div(d.C, h->CC);
     h->n_mgroups = ceil_div(d.M, h->K * h->WM);
-    h->lut_entries = h->n_slots * h->plane_stride;
-    const long long lds = (long long)h->n_slots * h->CC * h->NB * h->plane_stride + g->max_adelta + 8;
-    if (lds * 4 > kLdsBudgetBytes) return ESCOIN_ERANGE;
-    h->lds_floats = (int)lds;
+    // two window buffers (the next chunk is fetched while the current one is consumed) plus a
+    // zeroed tail that positions of the padded pitch past the last plane may read
+    const long long buf = (long long)h->n_slots * h->CC * h->NB * h->plane_stride;
+    if (buf * 8 > kLdsBudgetBytes) return ESCOIN_ERANGE;
+    h->buf_floats = (int)buf;
+    h->tail_floats = round_up(g->max_adelta + 8, 4);
+    if ((long long)h->NB * d.C * d.H * d.W >= (long long)INT32_MAX) return ESCOIN_ERANGE;
     if (h->WQ * h->WM > 8) return ESCOIN_ERANGE;  // at most 512 threads per workgroup
     return ESCOIN_OK;
 }
@@ -126,7 +134,7 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
         probe.CC = 1;
         const int lds_target = 64 * 1024;
         if (derive(d, &probe, &g) == ESCOIN_OK) {
-            const int per_c = probe.n_slots * probe.NB * probe.plane_stride * 4;
+            const int per_c = 2 * probe.n_slots * probe.NB * probe.plane_stride * 4;
             h->CC = std::max(1, std::min(d.C, lds_target / per_c));
             // equalise the chunks
             h->CC = ceil_div(d.C, ceil_div(d.C, h->CC));
@@ -143,36 +151,14 @@ struct RowNz {
 
 }  // namespace
 
-// Builds the plan into `out` (or only sizes it when out == nullptr).  Returns a code; the
-// byte count goes to *bytes.
-int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_t* stretched,
-               const float* value, const escoin_sconv_tuning* tuning, void* out, size_t out_bytes,
-               size_t* bytes) {
-    Dims d;
-    int rc = make_dims(desc, &d);
-    if (rc != ESCOIN_OK) return rc;
-    if (!rowptr || !bytes) return ESCOIN_EINVAL;
-    if (rowptr[0] != 0) return ESCOIN_EINVAL;
-    for (int m = 0; m < d.M; ++m)
-        if (rowptr[m + 1] < rowptr[m]) return ESCOIN_EINVAL;
-    const int nnz = rowptr[d.M];
-    if (nnz > 0 && (!stretched || (out && !value))) return ESCOIN_EINVAL;
-    if (tuning) {
-        const int32_t* f = &tuning->K;
-        for (int i = 0; i < 7; ++i)
-            if (f[i] < 0) return ESCOIN_EINVAL;
-    }
+namespace {
 
-    PlanHeader h;
-    std::memset(&h, 0, sizeof(h));
-    h.magic = kPlanMagic;
-    h.version = kPlanVersion;
-    h.C = d.C; h.H = d.H; h.W = d.W; h.M = d.M; h.R = d.R; h.S = d.S;
-    h.stride = d.stride; h.pad = d.pad; h.E = d.E; h.F = d.F;
-    choose_defaults(d, tuning, &h);
-    if (!tiled_variant_exists(h.K, h.Q, h.B)) return ESCOIN_EINVAL;
+// One attempt with the knobs in `h`.
+int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretched, const float* value,
+                    PlanHeader h, void* out, size_t out_bytes, size_t* bytes) {
+    const int nnz = rowptr[d.M];
     Geometry g;
-    rc = derive(d, &h, &g);
+    int rc = derive(d, &h, &g);
     if (rc != ESCOIN_OK) return rc;
     h.nnz = nnz;
 
@@ -212,43 +198,101 @@ int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_
         perm[((size_t)mg * h.WM + wm) * h.K + round] = order[i];
     }
 
-    // ---- count batches per (bin, chunk, k)
-    const int B = h.B;
-    const size_t seg_stride = 1 + (size_t)h.K;
-    std::vector<uint32_t> seg((size_t)bins * h.n_chunks * seg_stride, 0);
-    std::vector<int> cnt((size_t)h.n_chunks);
-    uint64_t total_batches = 0;
-    for (int b = 0; b < bins; ++b) {
-        // per-row, per-chunk counts
-        std::vector<std::vector<int>> rc_cnt(h.K, std::vector<int>(h.n_chunks, 0));
-        for (int k = 0; k < h.K; ++k) {
-            const int m = perm[(size_t)b * h.K + k];
-            if (m < 0) continue;
-            for (int j = rowptr[m]; j < rowptr[m + 1]; ++j) rc_cnt[k][nz_chunk[j]]++;
-        }
-        for (int ch = 0; ch < h.n_chunks; ++ch) {
-            uint32_t* sg = &seg[((size_t)b * h.n_chunks + ch) * seg_stride];
-            if (total_batches > 0xFFFFFFFFull) return ESCOIN_ERANGE;
-            sg[0] = (uint32_t)total_batches;
-            for (int k = 0; k < h.K; ++k) {
-                const int nb = ceil_div(rc_cnt[k][ch], B);
-                sg[1 + k] = (uint32_t)nb;
-                total_batches += nb;
+    // ---- staging items per tile: every input word the window needs and where it lives in LDS
+    const int threads = 64 * h.WQ * h.WM;
+    std::vector<std::vector<StageItem>> items(h.n_tiles);
+    const long long slot_stride = (long long)h.CC * h.NB * h.plane_stride;
+    for (int t = 0; t < h.n_tiles; ++t) {
+        const int h0 = t * h.TH;
+        for (int a = 0; a < d.stride; ++a) {
+            for (int b = 0; b < d.stride; ++b) {
+                int sl[kItemDsts], nsl = 0;
+                for (int i = 0; i < g.n_slots; ++i)
+                    if (g.slot_phase_a[i] == a && g.slot_phase_b[i] == b) {
+                        if (nsl == kItemDsts) return ESCOIN_ERANGE;
+                        sl[nsl++] = i;
+                    }
+                if (nsl == 0) continue;
+                for (int i = 0; i < h.rows_in; ++i) {
+                    const int y = (h0 + i) * d.stride + a - d.pad;
+                    if (y < 0 || y >= d.H) continue;
+                    for (int jx = 0; jx < h.pitch; ++jx) {
+                        const int x = jx * d.stride + b - d.pad;
+                        if (x < 0 || x >= d.W) continue;
+                        StageItem it;
+                        it.src = y * d.W + x;
+                        const int e0 = i * h.pitch + jx;
+                        bool any = false;
+                        for (int u = 0; u < kItemDsts; ++u) {
+                            it.dst[u] = -1;
+                            if (u < nsl && e0 - g.slot_shift[sl[u]] >= 0) {
+                                it.dst[u] = (int32_t)(sl[u] * slot_stride + e0 - g.slot_shift[sl[u]]);
+                                any = true;
+                            }
+                        }
+                        if (any) items[t].push_back(it);
+                    }
+                }
             }
         }
     }
-    const uint64_t n_records = (total_batches + 2) * B;  // two spare batches: the prefetch reads ahead
+    size_t n_items = 0;
+    for (auto& v : items) n_items = std::max(n_items, v.size());
+    n_items = std::max<size_t>(n_items, 1);
+    if ((long long)n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads) return ESCOIN_ERANGE;
+    h.n_items = (int32_t)n_items;
+
+    // ---- count batches per (group, chunk, wave, row); a group's chunk block is contiguous
+    const int B = h.B;
+    const size_t seg_stride = 1 + (size_t)h.K;
+    std::vector<uint32_t> seg((size_t)bins * h.n_chunks * seg_stride, 0);
+    std::vector<uint32_t> blk((size_t)h.n_mgroups * h.n_chunks * 2, 0);
+    std::vector<int> row_chunk_cnt((size_t)d.M * h.n_chunks, 0);
+    for (int m = 0; m < d.M; ++m)
+        for (int j = rowptr[m]; j < rowptr[m + 1]; ++j) row_chunk_cnt[(size_t)m * h.n_chunks + nz_chunk[j]]++;
+    uint64_t total_batches = 0, max_block = 0;
+    for (int mg = 0; mg < h.n_mgroups; ++mg) {
+        for (int ch = 0; ch < h.n_chunks; ++ch) {
+            if (total_batches > 0xFFFFFFF0ull) return ESCOIN_ERANGE;
+            const uint64_t block_start = total_batches;
+            for (int wm = 0; wm < h.WM; ++wm) {
+                const int bin = mg * h.WM + wm;
+                uint32_t* sg = &seg[((size_t)bin * h.n_chunks + ch) * seg_stride];
+                sg[0] = (uint32_t)(total_batches - block_start);
+                for (int k = 0; k < h.K; ++k) {
+                    const int m = perm[(size_t)bin * h.K + k];
+                    const int nb = m < 0 ? 0 : ceil_div(row_chunk_cnt[(size_t)m * h.n_chunks + ch], B);
+                    sg[1 + k] = (uint32_t)nb;
+                    total_batches += nb;
+                }
+            }
+            blk[((size_t)mg * h.n_chunks + ch) * 2] = (uint32_t)block_start;
+            blk[((size_t)mg * h.n_chunks + ch) * 2 + 1] = (uint32_t)(total_batches - block_start);
+            max_block = std::max(max_block, total_batches - block_start);
+        }
+    }
+    const uint64_t n_records = (total_batches + 2) * B;  // spare batches: copies round up, reads run ahead
     if (n_records > 0x7FFFFFFFull) return ESCOIN_ERANGE;
     h.n_records = (int32_t)n_records;
+    // one record buffer: the largest block, rounded to 16-byte copy units, plus the batch the
+    // record prefetch reads past a wave's last one
+    const uint64_t rec_buf = align_up64(max_block * B * 8 + (uint64_t)B * 8, 64);
+    if (rec_buf > (uint64_t)kMaxRecLoadsPerThread * threads * 16) return ESCOIN_ERANGE;
+    h.rec_buf_bytes = (int32_t)rec_buf;
+    const uint64_t lds_bytes = ((uint64_t)2 * h.buf_floats + h.tail_floats) * 4 + 2 * rec_buf;
+    if (lds_bytes > (uint64_t)kLdsBudgetBytes) return ESCOIN_ERANGE;
+    h.lds_bytes = (int32_t)lds_bytes;
 
     // ---- section layout
     uint64_t off = align_up64(sizeof(PlanHeader), 256);
-    h.off_src_lut = off;
-    off = align_up64(off + (uint64_t)h.n_tiles * h.lut_entries * 4, 256);
+    h.off_items = off;
+    off = align_up64(off + (uint64_t)h.n_tiles * h.n_items * sizeof(StageItem), 256);
     h.off_dst_lut = off;
     off = align_up64(off + (uint64_t)h.n_tiles * h.P4 * 4, 256);
     h.off_perm = off;
     off = align_up64(off + (uint64_t)perm.size() * 4, 256);
+    h.off_blk = off;
+    off = align_up64(off + (uint64_t)blk.size() * 4, 256);
     h.off_seg = off;
     off = align_up64(off + (uint64_t)seg.size() * 4, 256);
     h.off_rec = off;
@@ -262,24 +306,17 @@ int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_
     std::memset(base, 0, (size_t)off);
     std::memcpy(base, &h, sizeof(h));
 
-    // ---- src_lut / dst_lut
-    int32_t* src = (int32_t*)(base + h.off_src_lut);
+    // ---- items / dst_lut
+    StageItem* its = (StageItem*)(base + h.off_items);
     int32_t* dst = (int32_t*)(base + h.off_dst_lut);
     for (int t = 0; t < h.n_tiles; ++t) {
         const int h0 = t * h.TH;
-        for (int sl = 0; sl < h.n_slots; ++sl) {
-            int32_t* row = src + ((size_t)t * h.n_slots + sl) * h.plane_stride;
-            for (int e = 0; e < h.plane_stride; ++e) {
-                const int f = e + g.slot_shift[sl];
-                const int i = f / h.pitch, jx = f - i * h.pitch;
-                int32_t v = -1;
-                if (i < h.rows_in) {
-                    const int y = (h0 + i) * d.stride + g.slot_phase_a[sl] - d.pad;
-                    const int x = jx * d.stride + g.slot_phase_b[sl] - d.pad;
-                    if (y >= 0 && y < d.H && x >= 0 && x < d.W) v = y * d.W + x;
-                }
-                row[e] = v;
-            }
+        for (int i = 0; i < h.n_items; ++i) {
+            StageItem it;
+            it.src = -1;
+            for (int u = 0; u < kItemDsts; ++u) it.dst[u] = -1;
+            if ((size_t)i < items[t].size()) it = items[t][i];
+            its[(size_t)t * h.n_items + i] = it;
         }
         for (int p = 0; p < h.P4; ++p) {
             const int hh = p / h.pitch, w = p - hh * h.pitch;
@@ -288,25 +325,26 @@ int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_
         }
     }
     std::memcpy(base + h.off_perm, perm.data(), perm.size() * 4);
+    std::memcpy(base + h.off_blk, blk.data(), blk.size() * 4);
     std::memcpy(base + h.off_seg, seg.data(), seg.size() * 4);
 
-    // ---- records: per (bin, chunk, k) in CSR order, padded to whole batches with (0, 0.0f)
+    // ---- records: per (group, chunk, wave, row) in CSR order, padded to whole batches with
+    // (offset 0, value 0.0f)
     RowNz* rec = (RowNz*)(base + h.off_rec);
-    for (int b = 0; b < bins; ++b) {
-        std::vector<uint64_t> cursor((size_t)h.n_chunks * h.K);
-        for (int ch = 0; ch < h.n_chunks; ++ch) {
-            const uint32_t* sg = &seg[((size_t)b * h.n_chunks + ch) * seg_stride];
-            uint64_t at = (uint64_t)sg[0] * B;
-            for (int k = 0; k < h.K; ++k) {
-                cursor[(size_t)ch * h.K + k] = at;
-                at += (uint64_t)sg[1 + k] * B;
-            }
-        }
+    for (int bin = 0; bin < bins; ++bin) {
+        const int mg = bin / h.WM;
         for (int k = 0; k < h.K; ++k) {
-            const int m = perm[(size_t)b * h.K + k];
+            const int m = perm[(size_t)bin * h.K + k];
             if (m < 0) continue;
+            std::vector<uint64_t> cursor((size_t)h.n_chunks);
+            for (int ch = 0; ch < h.n_chunks; ++ch) {
+                const uint32_t* sg = &seg[((size_t)bin * h.n_chunks + ch) * seg_stride];
+                uint64_t at = (uint64_t)blk[((size_t)mg * h.n_chunks + ch) * 2] + sg[0];
+                for (int kk = 0; kk < k; ++kk) at += sg[1 + kk];
+                cursor[ch] = at * B;
+            }
             for (int j = rowptr[m]; j < rowptr[m + 1]; ++j) {
-                uint64_t& at = cursor[(size_t)nz_chunk[j] * h.K + k];
+                uint64_t& at = cursor[nz_chunk[j]];
                 rec[at].off_bytes = nz_off[j];
                 rec[at].val = value[j];
                 ++at;
@@ -314,6 +352,55 @@ int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_
         }
     }
     return ESCOIN_OK;
+}
+
+}  // namespace
+
+// Builds the plan into `out` (or only sizes it when out == nullptr).  Returns a code; the
+// byte count goes to *bytes.
+int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_t* stretched,
+               const float* value, const escoin_sconv_tuning* tuning, void* out, size_t out_bytes,
+               size_t* bytes) {
+    Dims d;
+    int rc = make_dims(desc, &d);
+    if (rc != ESCOIN_OK) return rc;
+    if (!rowptr || !bytes) return ESCOIN_EINVAL;
+    if (rowptr[0] != 0) return ESCOIN_EINVAL;
+    for (int m = 0; m < d.M; ++m)
+        if (rowptr[m + 1] < rowptr[m]) return ESCOIN_EINVAL;
+    const int nnz = rowptr[d.M];
+    if (nnz > 0 && (!stretched || (out && !value))) return ESCOIN_EINVAL;
+    if (tuning) {
+        const int32_t* f = &tuning->K;
+        for (int i = 0; i < 7; ++i)
+            if (f[i] < 0) return ESCOIN_EINVAL;
+    }
+
+    PlanHeader h;
+    std::memset(&h, 0, sizeof(h));
+    h.magic = kPlanMagic;
+    h.version = kPlanVersion;
+    h.C = d.C; h.H = d.H; h.W = d.W; h.M = d.M; h.R = d.R; h.S = d.S;
+    h.stride = d.stride; h.pad = d.pad; h.E = d.E; h.F = d.F;
+    choose_defaults(d, tuning, &h);
+    if (!tiled_variant_exists(h.K, h.Q, h.B)) return ESCOIN_EINVAL;
+    // Knobs the caller did not fix shrink until the window, the staging registers and the
+    // record block all fit: first the channel chunk, then the band height / images per group.
+    const bool auto_cc = !(tuning && tuning->CC > 0);
+    const bool auto_tile = !(tuning && (tuning->TH > 0 || tuning->NB > 0));
+    for (;;) {
+        rc = build_plan_once(d, rowptr, stretched, value, h, out, out_bytes, bytes);
+        if (rc != ESCOIN_ERANGE) return rc;
+        if (auto_cc && h.CC > 1) {
+            h.CC = std::max(1, h.CC * 3 / 4);
+        } else if (auto_tile && h.NB > 1) {
+            h.NB = h.NB / 2;
+        } else if (auto_tile && h.TH > 1) {
+            h.TH = (h.TH + 1) / 2;
+        } else {
+            return rc;
+        }
+    }
 }
 
 }  // namespace escoin

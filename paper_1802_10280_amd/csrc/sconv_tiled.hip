@@ -2,12 +2,17 @@
 //
 // One workgroup owns a tile of output positions (a band of rows of one image, or several
 // small images) and a group of output channels, and walks the input channels in chunks:
-//   stage   the chunk's input window is copied from the UNPADDED input into LDS through a
-//           lookup table that also supplies the zero frame (pad_in fused into the staging);
-//           the window is the flat padded array of Section 3.1, split into stride phases
-//           and stored once per 16-byte alignment class ("slot") of the filter taps;
-//   compute Algorithm 2 on that window: every wave streams the (LDS offset, value) records
-//           of its K CSR rows through the scalar data path; a lane owns 4*Q consecutive
+//   stage   the chunk's input window goes from the UNPADDED input to LDS through a table of
+//           (input word -> LDS words); the frame of zeros is written once at kernel start and
+//           never touched again, so pad_in is folded into the staging.  The window is the
+//           flat padded array of Section 3.1, split into stride phases and stored once per
+//           16-byte alignment class ("slot") of the filter taps.  The chunk's CSR records
+//           (LDS offset, value) of the workgroup's rows are copied to LDS as well (Section
+//           3.3 keeps colidx/value on chip).  Both are double-buffered: the global loads of
+//           chunk i+1 are issued before chunk i is consumed and land in registers meanwhile,
+//           so there is one barrier per chunk;
+//   compute Algorithm 2 on that window: a wave walks the records of its K CSR rows (every
+//           lane reads the same record: an LDS broadcast); a lane owns 4*Q consecutive
 //           positions of the flat array, fetches them with one aligned 16-byte LDS read per
 //           record and position group and accumulates val * in[off + f(0,h,w)] in registers;
 //   store   positions that are real outputs go to out[n][m][h][w] through the second table,
@@ -20,45 +25,58 @@
 namespace escoin {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
 struct TiledArgs {
     const float* in;
     float* out;
     const float* bias;
-    const int32_t* src_lut;
+    const StageItem* items;
     const int32_t* dst_lut;
     const int32_t* perm;
+    const uint32_t* blk;
     const uint32_t* seg;
     const uint32_t* rec;
     int N, C, HW, M, EF;
     int WM, WQ, CC, NB;
     int n_tiles, n_mgroups, n_chunks, n_in_tiles;
-    int plane_stride, P4, lut_entries;
+    int plane_stride, P4, n_items, buf_floats, tail_floats, rec_buf_bytes;
     uint32_t flags;
 };
 
 namespace {
 
-template <int B>
-struct Batch {
-    uint32_t w[2 * B];  // B x {LDS byte offset, value bits}
-};
+// Plan data that is wave-uniform and read-only for the whole launch is viewed through the
+// constant address space, which keeps those loads on the scalar data path.
+typedef const uint32_t __attribute__((address_space(4))) * cu32p;
+typedef const int32_t __attribute__((address_space(4))) * ci32p;
+__device__ __forceinline__ cu32p as_const(const uint32_t* p) { return (cu32p)(uintptr_t)p; }
+__device__ __forceinline__ ci32p as_const(const int32_t* p) { return (ci32p)(uintptr_t)p; }
 
 template <int B>
-__device__ __forceinline__ Batch<B> load_batch(const uint32_t* __restrict__ p) {
+struct Batch {
+    u4 w[B / 2];  // B x {LDS byte offset, value bits}, two records per 16 bytes
+};
+
+// Every lane reads the same 8*B bytes: an LDS broadcast.
+template <int B>
+__device__ __forceinline__ Batch<B> read_batch(const char* lds_bytes, int addr) {
     Batch<B> b;
 #pragma unroll
-    for (int i = 0; i < 2 * B; ++i) b.w[i] = p[i];  // uniform address: merged scalar loads
+    for (int i = 0; i < B / 2; ++i)
+        b.w[i] = *(const u4*)__builtin_assume_aligned(lds_bytes + addr + 16 * i, 16);
     return b;
 }
 
 template <int K, int Q, int B>
 __global__ __launch_bounds__(512) void sconv_tiled_kernel(const TiledArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
+    char* const lds_bytes = (char*)lds;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wq = wave % a.WQ, wm = wave / a.WQ;
+    const int nthreads = blockDim.x;
 
     // Workgroup -> (input tile, output-channel group).  Consecutive workgroup ids land on
     // different XCDs, so all channel groups of one input tile are given ids that are equal
@@ -70,6 +88,7 @@ __global__ __launch_bounds__(512) void sconv_tiled_kernel(const TiledArgs a) {
     const int tile = t_in % a.n_tiles;
     const int n0 = (t_in / a.n_tiles) * a.NB;
 
+    // ---- this lane's positions
     const int gpi = a.P4 >> 2;  // position groups per image
     int base_bytes[Q], nloc[Q], pos0[Q];
     bool active[Q];
@@ -83,65 +102,128 @@ __global__ __launch_bounds__(512) void sconv_tiled_kernel(const TiledArgs a) {
         base_bytes[q] = (nloc[q] * a.plane_stride + pos0[q]) * 4;
     }
 
+    // ---- this thread's share of the staging work; the same for every chunk
+    int st_src[kMaxItemsPerThread];                // offset from the chunk's first input word, -1 = none
+    int st_cl[kMaxItemsPerThread];                 // channel inside the chunk
+    int st_dst[kMaxItemsPerThread][kItemDsts];     // LDS byte offsets inside a window buffer, -1 = none
+    {
+        const StageItem* __restrict__ its = a.items + (size_t)tile * a.n_items;
+        const int total = a.n_items * a.CC * a.NB;
+#pragma unroll
+        for (int j = 0; j < kMaxItemsPerThread; ++j) {
+            const int idx = tid + j * nthreads;
+            st_src[j] = -1;
+            st_cl[j] = 0;
+#pragma unroll
+            for (int u = 0; u < kItemDsts; ++u) st_dst[j][u] = -1;
+            if (idx < total) {
+                const int cn = idx / a.n_items;
+                const StageItem it = its[idx - cn * a.n_items];
+                const int cl = cn / a.NB, nl = cn - cl * a.NB;
+                if (it.src >= 0 && n0 + nl < a.N) {
+                    st_src[j] = (nl * a.C + cl) * a.HW + it.src;
+                    st_cl[j] = cl;
+#pragma unroll
+                    for (int u = 0; u < kItemDsts; ++u)
+                        st_dst[j][u] = it.dst[u] >= 0 ? (it.dst[u] + cn * a.plane_stride) * 4 : -1;
+                }
+            }
+        }
+    }
+    const int win_bytes = a.buf_floats * 4;
+    const int rec_base = (2 * a.buf_floats + a.tail_floats) * 4;  // first record buffer
+    cu32p blkp = as_const(a.blk) + (size_t)mg * a.n_chunks * 2;
+    const int bin = mg * a.WM + wm;
+    cu32p segp = as_const(a.seg) + (size_t)bin * a.n_chunks * (1 + K);
+
+    float st_val[kMaxItemsPerThread];
+    u4 rc_val[kMaxRecLoadsPerThread];
+
+    // issue the global loads of chunk `ch` (window words and record block) into registers
+    auto fetch = [&](int ch) {
+        const int c0 = ch * a.CC;
+        const int ccur = min(a.CC, a.C - c0);
+        const float* __restrict__ src = a.in + ((size_t)n0 * a.C + c0) * a.HW;
+#pragma unroll
+        for (int j = 0; j < kMaxItemsPerThread; ++j)
+            if (st_src[j] >= 0 && st_cl[j] < ccur) st_val[j] = src[st_src[j]];
+        const u4* __restrict__ rsrc = (const u4*)(a.rec + (size_t)blkp[2 * ch] * (2 * B));
+        const int units = (int)blkp[2 * ch + 1] * (B / 2);  // 16-byte units in the block
+#pragma unroll
+        for (int j = 0; j < kMaxRecLoadsPerThread; ++j) {
+            const int u = tid + j * nthreads;
+            if (u < units) rc_val[j] = rsrc[u];
+        }
+    };
+    // write what fetch(ch) loaded into window / record buffer `buf`
+    auto commit = [&](int ch, int buf) {
+        const int ccur = min(a.CC, a.C - ch * a.CC);
+        char* const win = lds_bytes + buf * win_bytes;
+#pragma unroll
+        for (int j = 0; j < kMaxItemsPerThread; ++j)
+            if (st_src[j] >= 0 && st_cl[j] < ccur) {
+#pragma unroll
+                for (int u = 0; u < kItemDsts; ++u)
+                    if (st_dst[j][u] >= 0) *(float*)(win + st_dst[j][u]) = st_val[j];
+            }
+        const int units = (int)blkp[2 * ch + 1] * (B / 2);
+        char* const rb = lds_bytes + rec_base + buf * a.rec_buf_bytes;
+#pragma unroll
+        for (int j = 0; j < kMaxRecLoadsPerThread; ++j) {
+            const int u = tid + j * nthreads;
+            if (u < units) *(u4*)__builtin_assume_aligned(rb + 16 * u, 16) = rc_val[j];
+        }
+    };
+
+    fetch(0);
+    // The frame of zeros never changes: clear the window buffers and the tail once; from here
+    // on only words that hold input are rewritten, chunk after chunk.
+    for (int i = tid; i < 2 * a.buf_floats + a.tail_floats; i += nthreads) lds[i] = 0.0f;
+    __syncthreads();
+    commit(0, 0);
+    __syncthreads();
+
     f4 acc[K][Q];
 #pragma unroll
     for (int k = 0; k < K; ++k)
 #pragma unroll
         for (int q = 0; q < Q; ++q) acc[k][q] = (f4)(0.0f);
 
-    const int bin = mg * a.WM + wm;
-    const uint32_t* __restrict__ segp = a.seg + (size_t)bin * a.n_chunks * (1 + K);
-    const int32_t* __restrict__ lut = a.src_lut + (size_t)tile * a.lut_entries;
-    const int nthreads = blockDim.x;
-
     for (int ch = 0; ch < a.n_chunks; ++ch) {
-        __syncthreads();  // every wave is done reading the previous chunk
-        // ---- stage: LDS[slot][c][n][e] = in[n][c0+c][src_lut[slot][e]], 0 where the table says -1
-        const int c0 = ch * a.CC;
-        const int ccur = min(a.CC, a.C - c0);
-        for (int idx = tid; idx < a.lut_entries; idx += nthreads) {
-            const int s = lut[idx];
-            const int slot = idx / a.plane_stride;
-            const int e = idx - slot * a.plane_stride;
-            float* __restrict__ dst = lds + (size_t)slot * a.CC * a.NB * a.plane_stride + e;
-            const float* __restrict__ src = a.in + ((size_t)n0 * a.C + c0) * a.HW + (s >= 0 ? s : 0);
-            for (int nl = 0; nl < a.NB; ++nl) {
-                const bool ok = s >= 0 && n0 + nl < a.N;
-#pragma unroll 4
-                for (int cl = 0; cl < ccur; ++cl) {
-                    float v = 0.0f;
-                    if (ok) v = src[((size_t)nl * a.C + cl) * a.HW];
-                    dst[(cl * a.NB + nl) * a.plane_stride] = v;
-                }
-            }
-        }
-        __syncthreads();
+        const int buf = ch & 1;
+        const bool more = ch + 1 < a.n_chunks;
+        if (more) fetch(ch + 1);
 
         // ---- compute: Algorithm 2 over this chunk's nonzeros of the wave's K rows
-        const uint32_t* __restrict__ sg = segp + (size_t)ch * (1 + K);
-        const uint32_t* __restrict__ rp = a.rec + (size_t)sg[0] * (2 * B);
-        Batch<B> nxt = load_batch<B>(rp);
+        const int bufb = buf * win_bytes;
+        cu32p sg = segp + (size_t)ch * (1 + K);
+        int rptr = rec_base + buf * a.rec_buf_bytes + (int)sg[0] * (8 * B);
+        Batch<B> nxt = read_batch<B>(lds_bytes, rptr);
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const int cnt = (int)sg[1 + k];
             for (int b = 0; b < cnt; ++b) {
                 const Batch<B> cur = nxt;
-                rp += 2 * B;
-                nxt = load_batch<B>(rp);  // the stream has two spare batches at its end
+                rptr += 8 * B;
+                nxt = read_batch<B>(lds_bytes, rptr);  // at worst the spare batch after the block
                 f4 x[B][Q];
 #pragma unroll
                 for (int u = 0; u < B; ++u)
 #pragma unroll
                     for (int q = 0; q < Q; ++q)
                         x[u][q] = *(const f4*)__builtin_assume_aligned(
-                            (const char*)lds + (base_bytes[q] + (int)cur.w[2 * u]), 16);
+                            lds_bytes + (base_bytes[q] + bufb + (int)cur.w[u >> 1][(u & 1) * 2]), 16);
 #pragma unroll
                 for (int u = 0; u < B; ++u)
 #pragma unroll
                     for (int q = 0; q < Q; ++q)
-                        acc[k][q] += __uint_as_float(cur.w[2 * u + 1]) * x[u][q];
+                        acc[k][q] += __uint_as_float(cur.w[u >> 1][(u & 1) * 2 + 1]) * x[u][q];
             }
         }
+        // The other buffers were last read in the previous iteration, which every wave left
+        // through the barrier below: they can be rewritten now.
+        if (more) commit(ch + 1, buf ^ 1);
+        __syncthreads();
     }
 
     // ---- store
@@ -154,7 +236,7 @@ __global__ __launch_bounds__(512) void sconv_tiled_kernel(const TiledArgs a) {
             const int d = dlut[pos0[q] + i];
             dofs[q][i] = (active[q] && n0 + nloc[q] < a.N) ? d : -1;
         }
-    const int32_t* __restrict__ pm = a.perm + (size_t)bin * K;
+    ci32p pm = as_const(a.perm) + (size_t)bin * K;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const int m = pm[k];
@@ -224,15 +306,20 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     if (threads > 512 || threads <= 0) return ESCOIN_EINVAL;
     // the kernel's index arithmetic relies on these plan invariants
     if (h.P4 % 4 || h.plane_stride % 4 || h.P4 > h.plane_stride || h.NB < 1 || h.CC < 1 ||
-        h.lut_entries != h.n_slots * h.plane_stride || h.WQ * 64 * h.Q * 4 < h.NB * h.P4)
+        h.WQ * 64 * h.Q * 4 < h.NB * h.P4 || h.tail_floats % 4 || h.rec_buf_bytes % 16 ||
+        h.buf_floats != h.n_slots * h.CC * h.NB * h.plane_stride ||
+        (long long)h.n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads ||
+        h.rec_buf_bytes > kMaxRecLoadsPerThread * threads * 16 ||
+        h.lds_bytes != (2 * h.buf_floats + h.tail_floats) * 4 + 2 * h.rec_buf_bytes)
         return ESCOIN_EINVAL;
 
     const char* base = (const char*)d_plan;
     TiledArgs a;
     a.in = d_in; a.out = d_out; a.bias = d_bias;
-    a.src_lut = (const int32_t*)(base + h.off_src_lut);
+    a.items = (const StageItem*)(base + h.off_items);
     a.dst_lut = (const int32_t*)(base + h.off_dst_lut);
     a.perm = (const int32_t*)(base + h.off_perm);
+    a.blk = (const uint32_t*)(base + h.off_blk);
     a.seg = (const uint32_t*)(base + h.off_seg);
     a.rec = (const uint32_t*)(base + h.off_rec);
     a.N = d.N; a.C = d.C; a.HW = d.H * d.W; a.M = d.M; a.EF = d.E * d.F;
@@ -242,10 +329,11 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     const long long blocks = (n_in_tiles + 7) / 8 * 8 * h.n_mgroups;
     if (blocks > 0x7FFFFFFFll) return ESCOIN_ERANGE;
     a.n_in_tiles = (int)n_in_tiles;
-    a.plane_stride = h.plane_stride; a.P4 = h.P4; a.lut_entries = h.lut_entries;
+    a.plane_stride = h.plane_stride; a.P4 = h.P4; a.n_items = h.n_items;
+    a.buf_floats = h.buf_floats; a.tail_floats = h.tail_floats; a.rec_buf_bytes = h.rec_buf_bytes;
     a.flags = flags;
 
-    const size_t lds_bytes = (size_t)h.lds_floats * 4;
+    const size_t lds_bytes = (size_t)h.lds_bytes;
     if (lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void*)kern,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);

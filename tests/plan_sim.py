@@ -14,20 +14,27 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
     assert (C, H, W, M) == (h["C"], h["H"], h["W"], h["M"])
     K, B, WM, CC, NB = h["K"], h["B"], h["WM"], h["CC"], h["NB"]
     ps, P4, nslots = h["plane_stride"], h["P4"], h["n_slots"]
-    src = plan[h["off_src_lut"]:h["off_src_lut"] + 4 * h["n_tiles"] * h["lut_entries"]].view(np.int32)
-    src = src.reshape(h["n_tiles"], nslots, ps)
+    items = plan[h["off_items"]:h["off_items"] + 20 * h["n_tiles"] * h["n_items"]].view(np.int32)
+    items = items.reshape(h["n_tiles"], h["n_items"], 5)
     dst = plan[h["off_dst_lut"]:h["off_dst_lut"] + 4 * h["n_tiles"] * P4].view(np.int32).reshape(h["n_tiles"], P4)
     bins = h["n_mgroups"] * WM
     perm = plan[h["off_perm"]:h["off_perm"] + 4 * bins * K].view(np.int32).reshape(bins, K)
     seg = plan[h["off_seg"]:h["off_seg"] + 4 * bins * h["n_chunks"] * (1 + K)].view(np.uint32)
     seg = seg.reshape(bins, h["n_chunks"], 1 + K)
+    blk = plan[h["off_blk"]:h["off_blk"] + 8 * h["n_mgroups"] * h["n_chunks"]].view(np.uint32)
+    blk = blk.reshape(h["n_mgroups"], h["n_chunks"], 2)
     rec = plan[h["off_rec"]:h["off_rec"] + 8 * h["n_records"]]
     rec_off = rec.view(np.uint32)[0::2]
     rec_val = rec.view(np.float32)[1::2]
     assert sorted(perm[perm >= 0].tolist()) == list(range(M)), "perm must cover every row once"
     out = np.full((N, M, h["E"] * h["F"]), np.nan)
     xf = x.reshape(N, C, H * W).astype(np.float64)
-    lds_len = h["lds_floats"]
+    buf_floats = h["buf_floats"]
+    assert buf_floats == nslots * CC * NB * ps
+    lds_len = buf_floats + h["tail_floats"]            # one window buffer plus the zeroed tail
+    assert h["lds_bytes"] == (2 * buf_floats + h["tail_floats"]) * 4 + 2 * h["rec_buf_bytes"]
+    threads = 64 * h["WQ"] * WM
+    assert h["n_items"] * CC * NB <= 8 * threads
     pos = np.arange(P4)
     for t in range(h["n_tiles"]):
         for n0 in range(0, N, NB):
@@ -36,18 +43,25 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
             for ch in range(h["n_chunks"]):
                 c0 = ch * CC
                 ccur = min(CC, C - c0)
-                lds = np.full(lds_len, np.nan)      # unstaged LDS is garbage
-                win = np.zeros((nslots, CC, NB, ps))
-                win[:, ccur:] = np.nan
-                win[:, :, nb:] = 0.0
-                for sl in range(nslots):
-                    s = src[t, sl]
-                    ok = s >= 0
-                    v = np.where(ok[None, None, :], xf[n0:n0 + nb, c0:c0 + ccur][:, :, np.where(ok, s, 0)], 0.0)
-                    win[sl, :ccur, :nb] = v.transpose(1, 0, 2)
-                lds[:win.size] = win.ravel()
+                # the frame was zeroed once; the staging items rewrite the words that hold input
+                lds = np.zeros(lds_len)
+                it = items[t]
+                for sidx in range(h["n_items"]):
+                    s_src = it[sidx, 0]
+                    if s_src < 0:
+                        continue
+                    for u in range(4):
+                        d0 = it[sidx, 1 + u]
+                        if d0 < 0:
+                            continue
+                        for cl in range(ccur):
+                            for nl in range(nb):
+                                lds[d0 + (cl * NB + nl) * ps] = xf[n0 + nl, c0 + cl, s_src]
                 for b in range(bins):
-                    at = int(seg[b, ch, 0]) * B
+                    mgi = b // WM
+                    assert seg[b, ch, 0] + seg[b, ch, 1:].sum() <= blk[mgi, ch, 1]
+                    assert (int(blk[mgi, ch, 1]) + 1) * B * 8 <= h["rec_buf_bytes"]
+                    at = (int(blk[mgi, ch, 0]) + int(seg[b, ch, 0])) * B
                     for k in range(K):
                         cnt = int(seg[b, ch, 1 + k]) * B
                         for j in range(at, at + cnt):
