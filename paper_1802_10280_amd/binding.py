@@ -201,10 +201,11 @@ def escoin_sconv_forward_tiled(desc, plan_host: np.ndarray, d_plan, d_in, d_out,
 
 PLAN_HEADER_FIELDS = (
     ["magic", "version", "C", "H", "W", "M", "R", "S", "stride", "pad", "E", "F", "K", "Q", "B",
-     "WM", "WQ", "CC", "NB", "TH", "n_tiles", "n_mgroups", "n_chunks", "n_slots", "pitch",
+     "WM", "WQ", "CC", "NB", "TH", "n_tiles", "n_mgroups", "n_chunks", "n_phases", "pitch", "front",
      "rows_in", "plane_stride", "P4", "n_items", "buf_floats", "tail_floats", "rec_buf_bytes",
-     "lds_bytes", "nnz", "n_records", "reserved0"],
-    ["off_items", "off_dst_lut", "off_perm", "off_blk", "off_seg", "off_rec", "total_bytes"])
+     "lds_bytes", "nnz", "n_records"],
+    ["off_items", "off_lanes", "off_dst_lut", "off_perm", "off_blk", "off_seg", "off_rec",
+     "total_bytes"])
 
 
 def plan_header(plan: np.ndarray) -> dict:

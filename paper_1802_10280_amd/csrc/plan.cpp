@@ -2,22 +2,28 @@
 //
 // Input: the stretched CSR of escoin_sconv_pack (offsets into the padded CHW input, Section
 // 3.1).  Output: an opaque blob holding
-//   - two geometry tables, so the kernel needs no index arithmetic of its own:
+//   - geometry tables, so the kernel needs no index arithmetic of its own:
 //       items:   for every input word a tile's window needs, its offset in the (unpadded)
-//                input plane and the LDS words that hold it; words of the zero frame have no
+//                input plane and the LDS word that holds it; words of the zero frame have no
 //                item and stay +0.0f -- pad_in folded into the staging;
+//       lanes:   which 16-byte group of the window each lane of a wave reads and which four
+//                output positions it owns;
 //       dst_lut: for every computed position of a tile, where it goes in the E*F output plane
 //                (-1 = a position on the padded pitch that is not an output);
-//   - the nonzeros re-sorted per (output-channel group, channel chunk, wave, row), each with
-//     its LDS byte offset, so that the records a workgroup needs for one chunk are one
-//     contiguous block it can copy into LDS (Section 3.3 stages colidx/value on chip).
+//   - the nonzeros re-sorted per (output-channel group, channel chunk, wave, row, alignment
+//     class), each with its LDS byte offset, so that the records a workgroup needs for one
+//     chunk are one contiguous block it can copy into LDS (Section 3.3 stages colidx/value on
+//     chip).
 //
 // LDS window.  The padded input of a tile is split into stride*stride phase planes (phase =
-// coordinate mod stride), so that Algorithm 2's f(0,h,w) is h*pitch + w for every stride.  A
-// tap (r, s) reads phase (r % stride, s % stride) at delta = (r/stride)*pitch + s/stride from
-// the position.  Lanes own four consecutive positions and fetch them with one 16-byte LDS read;
-// to keep that read aligned for every tap, a phase plane is stored once per distinct
-// (delta mod 4), shifted left by that amount ("slot").
+// coordinate mod stride), so that Algorithm 2's f(0,h,w) is h*pitch + w for every stride; each
+// plane is `front` unused floats followed by rows of `pitch` floats.  A tap (r, s) of phase
+// (r % stride, s % stride) reads, for position p, the window word
+//     o + p,   o = front + (r / stride) * pitch + s / stride.
+// A lane owns four consecutive positions 4g .. 4g+3 and fetches the aligned 16 bytes at
+// 4g + (o - o % 4); the class o % 4 says how the four words it needs straddle that block and
+// the next one, which the neighbouring lane has fetched (the kernel moves it across with a
+// lane shift).  Class 3 is served from the following block and the previous lane instead.
 #include <limits.h>
 
 #include <algorithm>
@@ -39,37 +45,47 @@ inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
 inline uint64_t align_up64(uint64_t a, uint64_t b) { return (a + b - 1) / b * b; }
 
 constexpr int kLdsBudgetBytes = 160 * 1024;
+constexpr int kRunLanes = 62;  // lanes of a 64-lane run that own outputs (both ends only lend data)
 
 struct Geometry {
-    int n_slots = 0;
-    int slot_phase_a[kMaxSlots], slot_phase_b[kMaxSlots], slot_shift[kMaxSlots];
-    std::vector<int> tap_slot;    // [R*S]
-    std::vector<int> tap_adelta;  // [R*S] aligned part of delta (floats, multiple of 4)
-    int max_adelta = 0;
+    int n_phases = 0;
+    int phase_a[kMaxPhases], phase_b[kMaxPhases];
+    std::vector<int> tap_phase;  // [R*S] index into phase_*
+    std::vector<int> tap_class;  // [R*S] o % 4
+    std::vector<int> tap_aoff;   // [R*S] aligned word offset the lane adds to its group base
+    int max_aoff = 0;
 };
 
-int build_geometry(const Dims& d, int pitch, Geometry* g) {
-    g->tap_slot.assign((size_t)d.R * d.S, -1);
-    g->tap_adelta.assign((size_t)d.R * d.S, 0);
+// Cost of a class in lane-shift moves per record: 0, 1, 2 words from the next lane, or (class
+// 3) one word from the previous lane.
+inline int class_cost(int c) { return c == 0 ? 0 : (c == 2 ? 2 : 1); }
+
+int build_geometry(const Dims& d, int pitch, int front, Geometry* g) {
+    g->n_phases = 0;
+    g->tap_phase.assign((size_t)d.R * d.S, -1);
+    g->tap_class.assign((size_t)d.R * d.S, 0);
+    g->tap_aoff.assign((size_t)d.R * d.S, 0);
+    g->max_aoff = 0;
     for (int r = 0; r < d.R; ++r) {
         for (int s = 0; s < d.S; ++s) {
             const int a = r % d.stride, b = s % d.stride;
-            const int delta = (r / d.stride) * pitch + s / d.stride;
-            const int shift = delta % 4;
-            int slot = -1;
-            for (int i = 0; i < g->n_slots; ++i)
-                if (g->slot_phase_a[i] == a && g->slot_phase_b[i] == b && g->slot_shift[i] == shift)
-                    slot = i;
-            if (slot < 0) {
-                if (g->n_slots == kMaxSlots) return ESCOIN_ERANGE;
-                slot = g->n_slots++;
-                g->slot_phase_a[slot] = a;
-                g->slot_phase_b[slot] = b;
-                g->slot_shift[slot] = shift;
+            int ph = -1;
+            for (int i = 0; i < g->n_phases; ++i)
+                if (g->phase_a[i] == a && g->phase_b[i] == b) ph = i;
+            if (ph < 0) {
+                if (g->n_phases == kMaxPhases) return ESCOIN_ERANGE;
+                ph = g->n_phases++;
+                g->phase_a[ph] = a;
+                g->phase_b[ph] = b;
             }
-            g->tap_slot[(size_t)r * d.S + s] = slot;
-            g->tap_adelta[(size_t)r * d.S + s] = delta - shift;
-            g->max_adelta = std::max(g->max_adelta, delta - shift);
+            const int o = front + (r / d.stride) * pitch + s / d.stride;
+            const int cls = o % 4;
+            const int aoff = o - cls + (cls == 3 ? 4 : 0);
+            const size_t tap = (size_t)r * d.S + s;
+            g->tap_phase[tap] = ph;
+            g->tap_class[tap] = cls;
+            g->tap_aoff[tap] = aoff;
+            g->max_aoff = std::max(g->max_aoff, aoff);
         }
     }
     return ESCOIN_OK;
@@ -79,52 +95,69 @@ int build_geometry(const Dims& d, int pitch, Geometry* g) {
 int derive(const Dims& d, PlanHeader* h, Geometry* g) {
     const int cols_ph = ceil_div(d.Wp, d.stride);
     h->pitch = round_up(cols_ph, 4);
-    int rc = build_geometry(d, h->pitch, g);
+    // front padding: at least one whole group (the lane left of the first group reads it), and
+    // the residue that makes the taps' alignment classes cheapest
+    int best_front = 4, best_cost = INT_MAX;
+    for (int front = 4; front < 8; ++front) {
+        int cost = 0;
+        for (int r = 0; r < d.R; ++r)
+            for (int s = 0; s < d.S; ++s)
+                cost += class_cost((front + (r / d.stride) * h->pitch + s / d.stride) % 4);
+        if (cost < best_cost) {
+            best_cost = cost;
+            best_front = front;
+        }
+    }
+    h->front = best_front;
+    int rc = build_geometry(d, h->pitch, h->front, g);
     if (rc != ESCOIN_OK) return rc;
-    h->n_slots = g->n_slots;
+    h->n_phases = g->n_phases;
     h->TH = std::min(h->TH, d.E);
     h->n_tiles = ceil_div(d.E, h->TH);
     h->rows_in = h->TH + (d.R - 1) / d.stride;
-    h->plane_stride = round_up(h->rows_in * h->pitch + 4, 4);
+    h->plane_stride = round_up(h->front + h->rows_in * h->pitch + 4, 4);
     h->P4 = round_up(h->TH * h->pitch, 4);
-    const int groups = h->NB * (h->P4 / 4);
-    h->WQ = ceil_div(groups, 64 * h->Q);
+    // lanes: per image the groups -1 .. P4/4 (one lending group on either side); a run of 64
+    // lanes owns the outputs of its 62 inner lanes, so consecutive runs overlap by two entries
+    const int entries = h->NB * (h->P4 / 4 + 2);
+    const int runs = std::max(1, ceil_div(entries - 2, kRunLanes));
+    h->WQ = ceil_div(runs, h->Q);
     h->CC = std::min(h->CC, d.C);
     h->n_chunks = ceil_div(d.C, h->CC);
     h->n_mgroups = ceil_div(d.M, h->K * h->WM);
     // two window buffers (the next chunk is fetched while the current one is consumed) plus a
-    // zeroed tail that positions of the padded pitch past the last plane may read
-    const long long buf = (long long)h->n_slots * h->CC * h->NB * h->plane_stride;
+    // zeroed tail that lanes past the last plane may read
+    const long long buf = (long long)h->n_phases * h->CC * h->NB * h->plane_stride;
     if (buf * 8 > kLdsBudgetBytes) return ESCOIN_ERANGE;
     h->buf_floats = (int)buf;
-    h->tail_floats = round_up(g->max_adelta + 8, 4);
+    h->tail_floats = round_up(g->max_aoff + 16, 4);
     if ((long long)h->NB * d.C * d.H * d.W >= (long long)INT32_MAX) return ESCOIN_ERANGE;
-    if (h->WQ * h->WM > 8) return ESCOIN_ERANGE;  // at most 512 threads per workgroup
+    if (h->WQ * h->WM > 16) return ESCOIN_ERANGE;  // at most 1024 threads per workgroup
     return ESCOIN_OK;
 }
 
-// Default knobs.  Positions of NB images (or of one band of TH rows) fill the 64*Q*4 positions
-// of one wave; the channel chunk takes what LDS is left under `lds_target`.
+// Default knobs.  Positions of NB images (or of one band of TH rows) fill the position runs of
+// one wave; the channel chunk takes what LDS is left under `lds_target`.
 void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h) {
     const int cols_ph = ceil_div(d.Wp, d.stride);
     const int pitch = round_up(cols_ph, 4);
     h->Q = (t && t->Q > 0) ? t->Q : 1;
     h->B = (t && t->B > 0) ? t->B : 4;
-    h->K = (t && t->K > 0) ? t->K : 8;
-    const int wave_pos = 64 * h->Q * 4;
+    h->K = (t && t->K > 0) ? t->K : 4;
+    const int wave_groups = kRunLanes * h->Q;  // groups one wave can own
     // tile: whole image(s) when an image's positions fit one wave, else a band of rows
     int TH = d.E, NB = 1;
-    if (d.E * pitch <= wave_pos) {
-        NB = std::max(1, wave_pos / round_up(d.E * pitch, 4));
+    const int img_groups = d.E * pitch / 4 + 2;
+    if (img_groups - 2 <= wave_groups) {
+        NB = std::max(1, (wave_groups + 2) / img_groups);
         NB = std::min(NB, d.N);
     } else {
-        TH = std::max(1, wave_pos / pitch);
-        // even out the bands
-        TH = ceil_div(d.E, ceil_div(d.E, TH));
+        TH = std::max(1, wave_groups * 4 / pitch);
+        TH = ceil_div(d.E, ceil_div(d.E, TH));  // even out the bands
     }
     h->TH = (t && t->TH > 0) ? t->TH : TH;
     h->NB = (t && t->NB > 0) ? t->NB : ((t && t->TH > 0 && t->TH < d.E) ? 1 : NB);
-    int WM = std::min(8, ceil_div(d.M, h->K));
+    int WM = std::min(16, ceil_div(d.M, h->K));
     h->WM = (t && t->WM > 0) ? t->WM : WM;
     if (t && t->CC > 0) {
         h->CC = t->CC;
@@ -132,12 +165,11 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
         Geometry g;
         PlanHeader probe = *h;
         probe.CC = 1;
-        const int lds_target = 64 * 1024;
+        const int lds_target = 96 * 1024;
         if (derive(d, &probe, &g) == ESCOIN_OK) {
-            const int per_c = 2 * probe.n_slots * probe.NB * probe.plane_stride * 4;
+            const int per_c = 2 * probe.n_phases * probe.NB * probe.plane_stride * 4;
             h->CC = std::max(1, std::min(d.C, lds_target / per_c));
-            // equalise the chunks
-            h->CC = ceil_div(d.C, ceil_div(d.C, h->CC));
+            h->CC = ceil_div(d.C, ceil_div(d.C, h->CC));  // equalise the chunks
         } else {
             h->CC = 1;
         }
@@ -149,10 +181,6 @@ struct RowNz {
     float val;
 };
 
-}  // namespace
-
-namespace {
-
 // One attempt with the knobs in `h`.
 int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretched, const float* value,
                     PlanHeader h, void* out, size_t out_bytes, size_t* bytes) {
@@ -161,11 +189,12 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     int rc = derive(d, &h, &g);
     if (rc != ESCOIN_OK) return rc;
     h.nnz = nnz;
+    const int threads = 64 * h.WQ * h.WM;
 
-    // ---- decode every nonzero: stretched offset -> (c, r, s) -> (chunk, LDS byte offset)
+    // ---- decode every nonzero: stretched offset -> (c, r, s) -> (chunk, class, LDS byte offset)
     const int plane_in = d.Hp * d.Wp;
-    const int chan_stride = h.NB * h.plane_stride;  // floats between channels of one slot
-    std::vector<int> nz_chunk((size_t)nnz);
+    const int chan_stride = h.NB * h.plane_stride;  // floats between channels of one phase
+    std::vector<int> nz_chunk((size_t)nnz), nz_class((size_t)nnz);
     std::vector<uint32_t> nz_off((size_t)nnz);
     for (int j = 0; j < nnz; ++j) {
         const int off = stretched[j];
@@ -176,13 +205,15 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
         if (r >= d.R || s >= d.S) return ESCOIN_EINVAL;  // not an offset weight stretching makes
         const int chunk = c / h.CC, cl = c - chunk * h.CC;
         const int tap = r * d.S + s;
-        const long long fl = ((long long)g.tap_slot[tap] * h.CC + cl) * chan_stride + g.tap_adelta[tap];
+        const long long fl = ((long long)g.tap_phase[tap] * h.CC + cl) * chan_stride + g.tap_aoff[tap];
         nz_chunk[j] = chunk;
+        nz_class[j] = g.tap_class[tap];
         nz_off[j] = (uint32_t)(fl * 4);
     }
 
-    // ---- rows -> bins (one bin = the K accumulator rows of one wave), balanced by nnz:
-    // rows sorted by length are dealt out in snake order over all bins
+    // ---- rows -> bins (one bin = the K accumulator rows of one wave), balanced by nnz: rows in
+    // order of decreasing length each go to the bin with the least work so far that still has
+    // a free accumulator row.  Consecutive bins belong to different workgroups.
     const int bins = h.n_mgroups * h.WM;
     std::vector<int> order(d.M);
     std::iota(order.begin(), order.end(), 0);
@@ -190,48 +221,36 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
         return rowptr[a + 1] - rowptr[a] > rowptr[b + 1] - rowptr[b];
     });
     std::vector<int32_t> perm((size_t)bins * h.K, -1);
-    for (int i = 0; i < d.M; ++i) {
-        const int round = i / bins, pos = i % bins;
-        const int b = (round % 2 == 0) ? pos : bins - 1 - pos;
-        // consecutive bins go to different workgroups: bin index = wave * n_mgroups + group
-        const int mg = b % h.n_mgroups, wm = b / h.n_mgroups;
-        perm[((size_t)mg * h.WM + wm) * h.K + round] = order[i];
+    {
+        std::vector<long long> load(bins, 0);
+        std::vector<int> used(bins, 0);
+        for (int i = 0; i < d.M; ++i) {
+            int best = -1;
+            for (int b = 0; b < bins; ++b)
+                if (used[b] < h.K && (best < 0 || load[b] < load[best])) best = b;
+            const int mg = best % h.n_mgroups, wm = best / h.n_mgroups;
+            perm[((size_t)mg * h.WM + wm) * h.K + used[best]] = order[i];
+            load[best] += rowptr[order[i] + 1] - rowptr[order[i]] + 1;
+            used[best]++;
+        }
     }
 
     // ---- staging items per tile: every input word the window needs and where it lives in LDS
-    const int threads = 64 * h.WQ * h.WM;
     std::vector<std::vector<StageItem>> items(h.n_tiles);
-    const long long slot_stride = (long long)h.CC * h.NB * h.plane_stride;
+    const long long phase_stride = (long long)h.CC * h.NB * h.plane_stride;
     for (int t = 0; t < h.n_tiles; ++t) {
         const int h0 = t * h.TH;
-        for (int a = 0; a < d.stride; ++a) {
-            for (int b = 0; b < d.stride; ++b) {
-                int sl[kItemDsts], nsl = 0;
-                for (int i = 0; i < g.n_slots; ++i)
-                    if (g.slot_phase_a[i] == a && g.slot_phase_b[i] == b) {
-                        if (nsl == kItemDsts) return ESCOIN_ERANGE;
-                        sl[nsl++] = i;
-                    }
-                if (nsl == 0) continue;
-                for (int i = 0; i < h.rows_in; ++i) {
-                    const int y = (h0 + i) * d.stride + a - d.pad;
-                    if (y < 0 || y >= d.H) continue;
-                    for (int jx = 0; jx < h.pitch; ++jx) {
-                        const int x = jx * d.stride + b - d.pad;
-                        if (x < 0 || x >= d.W) continue;
-                        StageItem it;
-                        it.src = y * d.W + x;
-                        const int e0 = i * h.pitch + jx;
-                        bool any = false;
-                        for (int u = 0; u < kItemDsts; ++u) {
-                            it.dst[u] = -1;
-                            if (u < nsl && e0 - g.slot_shift[sl[u]] >= 0) {
-                                it.dst[u] = (int32_t)(sl[u] * slot_stride + e0 - g.slot_shift[sl[u]]);
-                                any = true;
-                            }
-                        }
-                        if (any) items[t].push_back(it);
-                    }
+        for (int ph = 0; ph < g.n_phases; ++ph) {
+            for (int i = 0; i < h.rows_in; ++i) {
+                const int y = (h0 + i) * d.stride + g.phase_a[ph] - d.pad;
+                if (y < 0 || y >= d.H) continue;
+                for (int jx = 0; jx < h.pitch; ++jx) {
+                    const int x = jx * d.stride + g.phase_b[ph] - d.pad;
+                    if (x < 0 || x >= d.W) continue;
+                    StageItem it;
+                    it.src = y * d.W + x;
+                    it.dst = (int32_t)(ph * phase_stride + h.front + i * h.pitch + jx);
+                    items[t].push_back(it);
                 }
             }
         }
@@ -242,14 +261,42 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     if ((long long)n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads) return ESCOIN_ERANGE;
     h.n_items = (int32_t)n_items;
 
-    // ---- count batches per (group, chunk, wave, row); a group's chunk block is contiguous
+    // ---- lanes of every position run
+    const int gpi = h.P4 / 4;
+    std::vector<LaneSlot> entries;
+    for (int nl = 0; nl < h.NB; ++nl)
+        for (int gi = -1; gi <= gpi; ++gi) {
+            LaneSlot e;
+            e.base_word = nl * h.plane_stride + 4 * gi;
+            e.pos0 = (gi >= 0 && gi < gpi) ? 4 * gi : -1;
+            e.nloc = nl;
+            entries.push_back(e);
+        }
+    const int runs = h.WQ * h.Q;
+    std::vector<LaneSlot> lanes((size_t)runs * 64);
+    for (int r = 0; r < runs; ++r)
+        for (int l = 0; l < 64; ++l) {
+            const size_t e = (size_t)r * kRunLanes + l;
+            LaneSlot s;
+            if (e < entries.size()) {
+                s = entries[e];
+                if (l == 0 || l == 63) s.pos0 = -1;  // run ends only lend their group
+            } else {  // idle lane: shadow the first real group, own nothing
+                s = entries[1];
+                s.pos0 = -1;
+            }
+            lanes[(size_t)r * 64 + l] = s;
+        }
+
+    // ---- count batches per (group, chunk, wave, row, class); a group's chunk block is contiguous
     const int B = h.B;
-    const size_t seg_stride = 1 + (size_t)h.K;
+    const size_t seg_stride = 1 + (size_t)h.K * kClasses;
     std::vector<uint32_t> seg((size_t)bins * h.n_chunks * seg_stride, 0);
     std::vector<uint32_t> blk((size_t)h.n_mgroups * h.n_chunks * 2, 0);
-    std::vector<int> row_chunk_cnt((size_t)d.M * h.n_chunks, 0);
+    std::vector<int> rcc((size_t)d.M * h.n_chunks * kClasses, 0);  // per row, chunk, class
     for (int m = 0; m < d.M; ++m)
-        for (int j = rowptr[m]; j < rowptr[m + 1]; ++j) row_chunk_cnt[(size_t)m * h.n_chunks + nz_chunk[j]]++;
+        for (int j = rowptr[m]; j < rowptr[m + 1]; ++j)
+            rcc[((size_t)m * h.n_chunks + nz_chunk[j]) * kClasses + nz_class[j]]++;
     uint64_t total_batches = 0, max_block = 0;
     for (int mg = 0; mg < h.n_mgroups; ++mg) {
         for (int ch = 0; ch < h.n_chunks; ++ch) {
@@ -261,9 +308,12 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
                 sg[0] = (uint32_t)(total_batches - block_start);
                 for (int k = 0; k < h.K; ++k) {
                     const int m = perm[(size_t)bin * h.K + k];
-                    const int nb = m < 0 ? 0 : ceil_div(row_chunk_cnt[(size_t)m * h.n_chunks + ch], B);
-                    sg[1 + k] = (uint32_t)nb;
-                    total_batches += nb;
+                    for (int cls = 0; cls < kClasses; ++cls) {
+                        const int nb =
+                            m < 0 ? 0 : ceil_div(rcc[((size_t)m * h.n_chunks + ch) * kClasses + cls], B);
+                        sg[1 + k * kClasses + cls] = (uint32_t)nb;
+                        total_batches += nb;
+                    }
                 }
             }
             blk[((size_t)mg * h.n_chunks + ch) * 2] = (uint32_t)block_start;
@@ -271,13 +321,12 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
             max_block = std::max(max_block, total_batches - block_start);
         }
     }
-    const uint64_t n_records = (total_batches + 2) * B;  // spare batches: copies round up, reads run ahead
+    const uint64_t n_records = (total_batches + 2) * B + 16;  // spare: copies round up, reads run ahead
     if (n_records > 0x7FFFFFFFull) return ESCOIN_ERANGE;
     h.n_records = (int32_t)n_records;
-    // one record buffer: the largest block, rounded to 16-byte copy units, plus the batch the
-    // record prefetch reads past a wave's last one
-    const uint64_t rec_buf = align_up64(max_block * B * 8 + (uint64_t)B * 8, 64);
-    if (rec_buf > (uint64_t)kMaxRecLoadsPerThread * threads * 16) return ESCOIN_ERANGE;
+    // one record buffer: the largest block plus the batch the record prefetch reads past a
+    // wave's last one
+    const uint64_t rec_buf = align_up64(max_block * B * 8 + (uint64_t)B * 8 + 16, 64);
     h.rec_buf_bytes = (int32_t)rec_buf;
     const uint64_t lds_bytes = ((uint64_t)2 * h.buf_floats + h.tail_floats) * 4 + 2 * rec_buf;
     if (lds_bytes > (uint64_t)kLdsBudgetBytes) return ESCOIN_ERANGE;
@@ -287,6 +336,8 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     uint64_t off = align_up64(sizeof(PlanHeader), 256);
     h.off_items = off;
     off = align_up64(off + (uint64_t)h.n_tiles * h.n_items * sizeof(StageItem), 256);
+    h.off_lanes = off;
+    off = align_up64(off + (uint64_t)lanes.size() * sizeof(LaneSlot), 256);
     h.off_dst_lut = off;
     off = align_up64(off + (uint64_t)h.n_tiles * h.P4 * 4, 256);
     h.off_perm = off;
@@ -306,7 +357,7 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     std::memset(base, 0, (size_t)off);
     std::memcpy(base, &h, sizeof(h));
 
-    // ---- items / dst_lut
+    // ---- items / lanes / dst_lut
     StageItem* its = (StageItem*)(base + h.off_items);
     int32_t* dst = (int32_t*)(base + h.off_dst_lut);
     for (int t = 0; t < h.n_tiles; ++t) {
@@ -314,7 +365,7 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
         for (int i = 0; i < h.n_items; ++i) {
             StageItem it;
             it.src = -1;
-            for (int u = 0; u < kItemDsts; ++u) it.dst[u] = -1;
+            it.dst = 0;
             if ((size_t)i < items[t].size()) it = items[t][i];
             its[(size_t)t * h.n_items + i] = it;
         }
@@ -324,27 +375,35 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
                 (hh < h.TH && h0 + hh < d.E && w < d.F) ? (h0 + hh) * d.F + w : -1;
         }
     }
+    std::memcpy(base + h.off_lanes, lanes.data(), lanes.size() * sizeof(LaneSlot));
     std::memcpy(base + h.off_perm, perm.data(), perm.size() * 4);
     std::memcpy(base + h.off_blk, blk.data(), blk.size() * 4);
     std::memcpy(base + h.off_seg, seg.data(), seg.size() * 4);
 
-    // ---- records: per (group, chunk, wave, row) in CSR order, padded to whole batches with
-    // (offset 0, value 0.0f)
+    // ---- records: per (group, chunk, wave, row, class) in CSR order, padded to whole batches
+    // with (offset of the first group, value 0.0f): a padding record reads valid LDS and adds 0
     RowNz* rec = (RowNz*)(base + h.off_rec);
+    for (uint64_t i = 0; i < n_records; ++i) {
+        rec[i].off_bytes = 16;
+        rec[i].val = 0.0f;
+    }
     for (int bin = 0; bin < bins; ++bin) {
         const int mg = bin / h.WM;
         for (int k = 0; k < h.K; ++k) {
             const int m = perm[(size_t)bin * h.K + k];
             if (m < 0) continue;
-            std::vector<uint64_t> cursor((size_t)h.n_chunks);
+            std::vector<uint64_t> cursor((size_t)h.n_chunks * kClasses);
             for (int ch = 0; ch < h.n_chunks; ++ch) {
                 const uint32_t* sg = &seg[((size_t)bin * h.n_chunks + ch) * seg_stride];
                 uint64_t at = (uint64_t)blk[((size_t)mg * h.n_chunks + ch) * 2] + sg[0];
-                for (int kk = 0; kk < k; ++kk) at += sg[1 + kk];
-                cursor[ch] = at * B;
+                for (int kk = 0; kk < k * kClasses; ++kk) at += sg[1 + kk];
+                for (int cls = 0; cls < kClasses; ++cls) {
+                    cursor[(size_t)ch * kClasses + cls] = at * B;
+                    at += sg[1 + k * kClasses + cls];
+                }
             }
             for (int j = rowptr[m]; j < rowptr[m + 1]; ++j) {
-                uint64_t& at = cursor[nz_chunk[j]];
+                uint64_t& at = cursor[(size_t)nz_chunk[j] * kClasses + nz_class[j]];
                 rec[at].off_bytes = nz_off[j];
                 rec[at].val = value[j];
                 ++at;

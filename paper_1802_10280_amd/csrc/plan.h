@@ -11,17 +11,23 @@
 namespace escoin {
 
 constexpr uint32_t kPlanMagic = 0x4E4C5045u;  // "EPLN"
-constexpr uint32_t kPlanVersion = 5;
-constexpr int kMaxSlots = 16;
-constexpr int kItemDsts = 4;       // a phase plane is stored under at most 4 alignment shifts
-constexpr int kMaxItemsPerThread = 8;   // staged input words per thread and chunk
-constexpr int kMaxRecLoadsPerThread = 4;  // 16-byte record units per thread and chunk
+constexpr uint32_t kPlanVersion = 7;
+constexpr int kMaxPhases = 16;          // stride*stride phase planes
+constexpr int kClasses = 4;             // alignment classes of a tap: (LDS offset) mod 4
+constexpr int kMaxItemsPerThread = 6;   // staged input words per thread and chunk
 
-// One input word of a tile's window and the LDS words (one per alignment slot of its phase
-// plane) that hold it, for channel 0 / image 0 of a window buffer; -1 = unused.
+// One input word of a tile's window: where it comes from and the LDS word that holds it (for
+// channel 0 / image 0 of a window buffer).
 struct StageItem {
-    int32_t src;              // offset inside an H*W input plane
-    int32_t dst[kItemDsts];   // word index inside a window buffer
+    int32_t src;  // offset inside an H*W input plane, -1 = padding entry of the table
+    int32_t dst;  // word index inside a window buffer
+};
+
+// What one lane of a position run does: the 16-byte group it reads and the outputs it owns.
+struct LaneSlot {
+    int32_t base_word;  // word index of the group inside a (channel 0) plane set
+    int32_t pos0;       // first of its 4 positions inside the image's tile, -1 = nothing to store
+    int32_t nloc;       // image inside the workgroup's image group
 };
 
 struct PlanHeader {
@@ -30,17 +36,18 @@ struct PlanHeader {
     int32_t C, H, W, M, R, S, stride, pad, E, F;
     // tiling
     int32_t K;   // output channels (CSR rows) accumulated per wave
-    int32_t Q;   // float4 position groups per lane
+    int32_t Q;   // position runs (one 16-byte group per lane each) per wave
     int32_t B;   // nonzero records per batch
     int32_t WM;  // waves of a workgroup along the output-channel axis
     int32_t WQ;  // waves of a workgroup along the position axis
     int32_t CC;  // input channels staged in LDS per chunk
     int32_t NB;  // images per workgroup
     int32_t TH;  // output rows per tile (band height)
-    int32_t n_tiles, n_mgroups, n_chunks, n_slots;
+    int32_t n_tiles, n_mgroups, n_chunks, n_phases;
     int32_t pitch;         // row pitch of a phase plane in LDS (floats, multiple of 4)
+    int32_t front;         // unused floats in front of every LDS plane
     int32_t rows_in;       // phase-plane rows held per tile
-    int32_t plane_stride;  // floats per (slot, channel, image) plane in LDS (multiple of 4)
+    int32_t plane_stride;  // floats per (phase, channel, image) plane in LDS (multiple of 4)
     int32_t P4;            // output positions per image and tile on the pitch grid (multiple of 4)
     int32_t n_items;       // StageItems per tile (shorter tiles are padded with src = -1)
     int32_t buf_floats;    // floats of one LDS window buffer (two are allocated)
@@ -48,13 +55,14 @@ struct PlanHeader {
     int32_t rec_buf_bytes; // bytes of one LDS record buffer (two are allocated)
     int32_t lds_bytes;     // dynamic LDS size
     int32_t nnz, n_records;
-    int32_t reserved0;
     // section offsets in bytes from the start of the blob
     uint64_t off_items;    // StageItem [n_tiles][n_items]
+    uint64_t off_lanes;    // LaneSlot [WQ*Q][64]
     uint64_t off_dst_lut;  // int32 [n_tiles][P4]: offset in an E*F plane, or -1
     uint64_t off_perm;     // int32 [n_mgroups*WM][K]: output channel of each accumulator row, or -1
     uint64_t off_blk;      // uint32 [n_mgroups][n_chunks][2]: first batch, batches of the group's block
-    uint64_t off_seg;      // uint32 [n_mgroups*WM][n_chunks][1+K]: first batch inside the block, batches per row
+    uint64_t off_seg;      // uint32 [n_mgroups*WM][n_chunks][1+K*kClasses]: first batch inside the
+                           // block, then batches per (row, class)
     uint64_t off_rec;      // {uint32 lds_byte_offset, float value} records, B per batch
     uint64_t total_bytes;
     uint32_t reserved[8];

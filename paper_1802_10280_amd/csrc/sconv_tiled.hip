@@ -3,18 +3,20 @@
 // One workgroup owns a tile of output positions (a band of rows of one image, or several
 // small images) and a group of output channels, and walks the input channels in chunks:
 //   stage   the chunk's input window goes from the UNPADDED input to LDS through a table of
-//           (input word -> LDS words); the frame of zeros is written once at kernel start and
+//           (input word -> LDS word); the frame of zeros is written once at kernel start and
 //           never touched again, so pad_in is folded into the staging.  The window is the
-//           flat padded array of Section 3.1, split into stride phases and stored once per
-//           16-byte alignment class ("slot") of the filter taps.  The chunk's CSR records
-//           (LDS offset, value) of the workgroup's rows are copied to LDS as well (Section
-//           3.3 keeps colidx/value on chip).  Both are double-buffered: the global loads of
-//           chunk i+1 are issued before chunk i is consumed and land in registers meanwhile,
-//           so there is one barrier per chunk;
+//           flat padded array of Section 3.1, one plane per stride phase.  The chunk's CSR
+//           records (LDS offset, value) of the workgroup's rows are copied to LDS as well
+//           (Section 3.3 keeps colidx/value on chip).  Both are double-buffered: the global
+//           loads of chunk i+1 are issued before chunk i is consumed (window words wait in
+//           registers, records go global -> LDS directly), so there is one barrier per chunk;
 //   compute Algorithm 2 on that window: a wave walks the records of its K CSR rows (every
-//           lane reads the same record: an LDS broadcast); a lane owns 4*Q consecutive
-//           positions of the flat array, fetches them with one aligned 16-byte LDS read per
-//           record and position group and accumulates val * in[off + f(0,h,w)] in registers;
+//           lane reads the same record: an LDS broadcast); a lane owns 4 consecutive
+//           positions of the flat array per position run.  For each record it fetches the
+//           aligned 16 bytes that hold most of the four words val multiplies; the words that
+//           fall into the neighbouring 16-byte group are taken from the neighbouring lane,
+//           which has just fetched them, with a lane shift (DPP) instead of a second LDS
+//           read.  Records are grouped by that alignment class so the shift is static code;
 //   store   positions that are real outputs go to out[n][m][h][w] through the second table,
 //           with the optional bias + ReLU epilogue.
 // Consecutive lanes own consecutive positions (the data-to-thread mapping of Section 3.2), so
@@ -32,6 +34,7 @@ struct TiledArgs {
     float* out;
     const float* bias;
     const StageItem* items;
+    const LaneSlot* lanes;
     const int32_t* dst_lut;
     const int32_t* perm;
     const uint32_t* blk;
@@ -53,6 +56,26 @@ typedef const int32_t __attribute__((address_space(4))) * ci32p;
 __device__ __forceinline__ cu32p as_const(const uint32_t* p) { return (cu32p)(uintptr_t)p; }
 __device__ __forceinline__ ci32p as_const(const int32_t* p) { return (ci32p)(uintptr_t)p; }
 
+// Value of `v` in the next lane (lane 63 gets 0) / in the previous lane (lane 0 gets 0).
+__device__ __forceinline__ float from_next_lane(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x130 /* wave_shl:1 */, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float from_prev_lane(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
+}
+
+// The four words a record of alignment class CLS multiplies, given the aligned group `x` this
+// lane fetched (its neighbours fetched the adjacent groups at the same time).
+template <int CLS>
+__device__ __forceinline__ f4 window_words(f4 x) {
+    if (CLS == 0) return x;
+    if (CLS == 1) return (f4){x[1], x[2], x[3], from_next_lane(x[0])};
+    if (CLS == 2) return (f4){x[2], x[3], from_next_lane(x[0]), from_next_lane(x[1])};
+    return (f4){from_prev_lane(x[3]), x[0], x[1], x[2]};
+}
+
 template <int B>
 struct Batch {
     u4 w[B / 2];  // B x {LDS byte offset, value bits}, two records per 16 bytes
@@ -68,8 +91,14 @@ __device__ __forceinline__ Batch<B> read_batch(const char* lds_bytes, int addr) 
     return b;
 }
 
-template <int K, int Q, int B>
-__global__ __launch_bounds__(512) void sconv_tiled_kernel(const TiledArgs a) {
+// byte distance between the groups one lane reads in consecutive position runs of a tile that
+// holds a single image (62 groups of 16 bytes)
+constexpr int kRunStrideBytes = 62 * 16;
+
+// CONTIG: the workgroup's tile holds one image, so a lane's groups in consecutive position runs
+// are kRunStrideBytes apart and the second LDS read needs no address arithmetic of its own.
+template <int K, int Q, int B, bool CONTIG>
+__global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     char* const lds_bytes = (char*)lds;
     const int tid = threadIdx.x;
@@ -88,24 +117,21 @@ __global__ __launch_bounds__(512) void sconv_tiled_kernel(const TiledArgs a) {
     const int tile = t_in % a.n_tiles;
     const int n0 = (t_in / a.n_tiles) * a.NB;
 
-    // ---- this lane's positions
-    const int gpi = a.P4 >> 2;  // position groups per image
+    // ---- this lane's group and positions in each of the wave's position runs
     int base_bytes[Q], nloc[Q], pos0[Q];
-    bool active[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
-        const int g = (wq * Q + q) * 64 + lane;
-        active[q] = g < a.NB * gpi;
-        const int gg = active[q] ? g : 0;  // idle lanes shadow group 0 (reads stay in range)
-        nloc[q] = gg / gpi;
-        pos0[q] = (gg - nloc[q] * gpi) * 4;
-        base_bytes[q] = (nloc[q] * a.plane_stride + pos0[q]) * 4;
+        const LaneSlot ls = a.lanes[((size_t)(wq * Q + q)) * 64 + lane];
+        base_bytes[q] = ls.base_word * 4;
+        nloc[q] = ls.nloc;
+        pos0[q] = ls.pos0;
     }
+    const int base0 = base_bytes[0];
 
     // ---- this thread's share of the staging work; the same for every chunk
-    int st_src[kMaxItemsPerThread];                // offset from the chunk's first input word, -1 = none
-    int st_cl[kMaxItemsPerThread];                 // channel inside the chunk
-    int st_dst[kMaxItemsPerThread][kItemDsts];     // LDS byte offsets inside a window buffer, -1 = none
+    int st_src[kMaxItemsPerThread];  // offset from the chunk's first input word, -1 = none
+    // bits 0..23: LDS byte offset of the word inside a window buffer; 24..31: channel in the chunk
+    uint32_t st_key[kMaxItemsPerThread];
     {
         const StageItem* __restrict__ its = a.items + (size_t)tile * a.n_items;
         const int total = a.n_items * a.CC * a.NB;
@@ -113,19 +139,14 @@ __global__ __launch_bounds__(512) void sconv_tiled_kernel(const TiledArgs a) {
         for (int j = 0; j < kMaxItemsPerThread; ++j) {
             const int idx = tid + j * nthreads;
             st_src[j] = -1;
-            st_cl[j] = 0;
-#pragma unroll
-            for (int u = 0; u < kItemDsts; ++u) st_dst[j][u] = -1;
+            st_key[j] = 0;
             if (idx < total) {
                 const int cn = idx / a.n_items;
                 const StageItem it = its[idx - cn * a.n_items];
                 const int cl = cn / a.NB, nl = cn - cl * a.NB;
                 if (it.src >= 0 && n0 + nl < a.N) {
                     st_src[j] = (nl * a.C + cl) * a.HW + it.src;
-                    st_cl[j] = cl;
-#pragma unroll
-                    for (int u = 0; u < kItemDsts; ++u)
-                        st_dst[j][u] = it.dst[u] >= 0 ? (it.dst[u] + cn * a.plane_stride) * 4 : -1;
+                    st_key[j] = (uint32_t)((it.dst + cn * a.plane_stride) * 4) | ((uint32_t)cl << 24);
                 }
             }
         }
@@ -134,53 +155,46 @@ __global__ __launch_bounds__(512) void sconv_tiled_kernel(const TiledArgs a) {
     const int rec_base = (2 * a.buf_floats + a.tail_floats) * 4;  // first record buffer
     cu32p blkp = as_const(a.blk) + (size_t)mg * a.n_chunks * 2;
     const int bin = mg * a.WM + wm;
-    cu32p segp = as_const(a.seg) + (size_t)bin * a.n_chunks * (1 + K);
+    constexpr int kSeg = 1 + K * kClasses;
+    cu32p segp = as_const(a.seg) + (size_t)bin * a.n_chunks * kSeg;
 
     float st_val[kMaxItemsPerThread];
-    u4 rc_val[kMaxRecLoadsPerThread];
 
-    // issue the global loads of chunk `ch` (window words and record block) into registers
-    auto fetch = [&](int ch) {
+    // Issue the global loads of chunk `ch`: window words into registers, the record block
+    // straight into record buffer `buf` (global_load ... lds, 16 bytes per lane, no registers).
+    auto fetch = [&](int ch, int buf) {
         const int c0 = ch * a.CC;
         const int ccur = min(a.CC, a.C - c0);
         const float* __restrict__ src = a.in + ((size_t)n0 * a.C + c0) * a.HW;
 #pragma unroll
         for (int j = 0; j < kMaxItemsPerThread; ++j)
-            if (st_src[j] >= 0 && st_cl[j] < ccur) st_val[j] = src[st_src[j]];
-        const u4* __restrict__ rsrc = (const u4*)(a.rec + (size_t)blkp[2 * ch] * (2 * B));
+            if (st_src[j] >= 0 && (int)(st_key[j] >> 24) < ccur) st_val[j] = src[st_src[j]];
+        const char* rsrc = (const char*)(a.rec + (size_t)blkp[2 * ch] * (2 * B));
         const int units = (int)blkp[2 * ch + 1] * (B / 2);  // 16-byte units in the block
-#pragma unroll
-        for (int j = 0; j < kMaxRecLoadsPerThread; ++j) {
-            const int u = tid + j * nthreads;
-            if (u < units) rc_val[j] = rsrc[u];
+        char* const rb = lds_bytes + rec_base + buf * a.rec_buf_bytes;
+        for (int u0 = wave * 64; u0 < units; u0 += nthreads) {  // u0: wave-uniform
+            if (u0 + lane < units)
+                __builtin_amdgcn_global_load_lds((const void*)(rsrc + 16 * (size_t)(u0 + lane)),
+                                                 (void __attribute__((address_space(3)))*)(rb + 16 * u0), 16, 0, 0);
         }
     };
-    // write what fetch(ch) loaded into window / record buffer `buf`
+    // Write the window words fetch(ch) loaded into window buffer `buf`.
     auto commit = [&](int ch, int buf) {
         const int ccur = min(a.CC, a.C - ch * a.CC);
         char* const win = lds_bytes + buf * win_bytes;
 #pragma unroll
         for (int j = 0; j < kMaxItemsPerThread; ++j)
-            if (st_src[j] >= 0 && st_cl[j] < ccur) {
-#pragma unroll
-                for (int u = 0; u < kItemDsts; ++u)
-                    if (st_dst[j][u] >= 0) *(float*)(win + st_dst[j][u]) = st_val[j];
-            }
-        const int units = (int)blkp[2 * ch + 1] * (B / 2);
-        char* const rb = lds_bytes + rec_base + buf * a.rec_buf_bytes;
-#pragma unroll
-        for (int j = 0; j < kMaxRecLoadsPerThread; ++j) {
-            const int u = tid + j * nthreads;
-            if (u < units) *(u4*)__builtin_assume_aligned(rb + 16 * u, 16) = rc_val[j];
-        }
+            if (st_src[j] >= 0 && (int)(st_key[j] >> 24) < ccur)
+                *(float*)(win + (st_key[j] & 0xFFFFFF)) = st_val[j];
     };
 
-    fetch(0);
+    fetch(0, 0);
     // The frame of zeros never changes: clear the window buffers and the tail once; from here
     // on only words that hold input are rewritten, chunk after chunk.
     for (int i = tid; i < 2 * a.buf_floats + a.tail_floats; i += nthreads) lds[i] = 0.0f;
     __syncthreads();
     commit(0, 0);
+    __builtin_amdgcn_s_waitcnt(0);  // this wave's record copies have landed
     __syncthreads();
 
     f4 acc[K][Q];
@@ -192,37 +206,61 @@ __global__ __launch_bounds__(512) void sconv_tiled_kernel(const TiledArgs a) {
     for (int ch = 0; ch < a.n_chunks; ++ch) {
         const int buf = ch & 1;
         const bool more = ch + 1 < a.n_chunks;
-        if (more) fetch(ch + 1);
+        if (more) fetch(ch + 1, buf ^ 1);
 
         // ---- compute: Algorithm 2 over this chunk's nonzeros of the wave's K rows
         const int bufb = buf * win_bytes;
-        cu32p sg = segp + (size_t)ch * (1 + K);
-        int rptr = rec_base + buf * a.rec_buf_bytes + (int)sg[0] * (8 * B);
-        Batch<B> nxt = read_batch<B>(lds_bytes, rptr);
+        cu32p sg = segp + (size_t)ch * kSeg;
+        // all segment lengths of the chunk in one scalar load, not one load per segment
+        uint32_t cnts[kSeg];
+#pragma unroll
+        for (int i = 0; i < kSeg; ++i) cnts[i] = sg[i];
+        int rptr = rec_base + buf * a.rec_buf_bytes + (int)cnts[0] * (8 * B);
+        // Two record batches ping-pong between `ra` and `rb`: while one is consumed the next
+        // one is already being read, and no register copies are needed to rotate them.
+        Batch<B> ra = read_batch<B>(lds_bytes, rptr), rb;
+        auto step = [&](auto cls_tag, f4(&ak)[Q], const Batch<B>& cur, Batch<B>& nxt) {
+            constexpr int CLS = decltype(cls_tag)::value;
+            rptr += 8 * B;
+            nxt = read_batch<B>(lds_bytes, rptr);  // at worst the spare batch after the block
+            f4 x[B][Q];
+#pragma unroll
+            for (int u = 0; u < B; ++u) {
+                const int at = base0 + bufb + (int)cur.w[u >> 1][(u & 1) * 2];
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+                    x[u][q] = *(const f4*)__builtin_assume_aligned(
+                        lds_bytes + (CONTIG ? at + q * kRunStrideBytes : at + (base_bytes[q] - base0)), 16);
+            }
+#pragma unroll
+            for (int u = 0; u < B; ++u)
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+                    ak[q] += __uint_as_float(cur.w[u >> 1][(u & 1) * 2 + 1]) * window_words<CLS>(x[u][q]);
+        };
+        auto run_class = [&](auto cls_tag, f4(&ak)[Q], int cnt) {
+            int b = 0;
+#pragma unroll 1
+            for (; b + 2 <= cnt; b += 2) {
+                step(cls_tag, ak, ra, rb);
+                step(cls_tag, ak, rb, ra);
+            }
+            if (b < cnt) {
+                step(cls_tag, ak, ra, rb);
+                ra = rb;
+            }
+        };
 #pragma unroll
         for (int k = 0; k < K; ++k) {
-            const int cnt = (int)sg[1 + k];
-            for (int b = 0; b < cnt; ++b) {
-                const Batch<B> cur = nxt;
-                rptr += 8 * B;
-                nxt = read_batch<B>(lds_bytes, rptr);  // at worst the spare batch after the block
-                f4 x[B][Q];
-#pragma unroll
-                for (int u = 0; u < B; ++u)
-#pragma unroll
-                    for (int q = 0; q < Q; ++q)
-                        x[u][q] = *(const f4*)__builtin_assume_aligned(
-                            lds_bytes + (base_bytes[q] + bufb + (int)cur.w[u >> 1][(u & 1) * 2]), 16);
-#pragma unroll
-                for (int u = 0; u < B; ++u)
-#pragma unroll
-                    for (int q = 0; q < Q; ++q)
-                        acc[k][q] += __uint_as_float(cur.w[u >> 1][(u & 1) * 2 + 1]) * x[u][q];
-            }
+            run_class(std::integral_constant<int, 0>{}, acc[k], (int)cnts[1 + k * kClasses + 0]);
+            run_class(std::integral_constant<int, 1>{}, acc[k], (int)cnts[1 + k * kClasses + 1]);
+            run_class(std::integral_constant<int, 2>{}, acc[k], (int)cnts[1 + k * kClasses + 2]);
+            run_class(std::integral_constant<int, 3>{}, acc[k], (int)cnts[1 + k * kClasses + 3]);
         }
         // The other buffers were last read in the previous iteration, which every wave left
         // through the barrier below: they can be rewritten now.
         if (more) commit(ch + 1, buf ^ 1);
+        __builtin_amdgcn_s_waitcnt(0);  // this wave's record copies have landed
         __syncthreads();
     }
 
@@ -233,8 +271,9 @@ __global__ __launch_bounds__(512) void sconv_tiled_kernel(const TiledArgs a) {
     for (int q = 0; q < Q; ++q)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int d = dlut[pos0[q] + i];
-            dofs[q][i] = (active[q] && n0 + nloc[q] < a.N) ? d : -1;
+            int d = -1;
+            if (pos0[q] >= 0 && n0 + nloc[q] < a.N) d = dlut[pos0[q] + i];
+            dofs[q][i] = d;
         }
     ci32p pm = as_const(a.perm) + (size_t)bin * K;
 #pragma unroll
@@ -257,21 +296,20 @@ __global__ __launch_bounds__(512) void sconv_tiled_kernel(const TiledArgs a) {
 
 typedef void (*TiledKernel)(const TiledArgs);
 
+// (K, Q, B) instantiations: the ones that fit 128 VGPRs (four waves per SIMD) without spilling.
+#define ESCOIN_TILED_VARIANTS(X) \
+    X(2, 1, 2) X(2, 1, 4) X(2, 2, 2) X(2, 2, 4) X(4, 1, 2) X(4, 1, 4) X(4, 2, 2) X(4, 2, 4) X(8, 1, 2) X(8, 1, 4) X(8, 2, 2)
+
 template <int K, int Q, int B>
-TiledKernel instance() {
-    return sconv_tiled_kernel<K, Q, B>;
+TiledKernel instance(bool contig) {
+    if (Q > 1 && contig) return sconv_tiled_kernel<K, Q, B, true>;
+    return sconv_tiled_kernel<K, Q, B, false>;
 }
 
-TiledKernel pick(int K, int Q, int B) {
-#define ESCOIN_PICK(KK)                                                   \
-    if (K == KK) {                                                        \
-        if (Q == 1) return B == 4 ? instance<KK, 1, 4>() : instance<KK, 1, 8>(); \
-        return B == 4 ? instance<KK, 2, 4>() : instance<KK, 2, 8>();      \
-    }
-    ESCOIN_PICK(2)
-    ESCOIN_PICK(4)
-    ESCOIN_PICK(8)
-    ESCOIN_PICK(16)
+TiledKernel pick(int K, int Q, int B, bool contig) {
+#define ESCOIN_PICK(KK, QQ, BB) \
+    if (K == KK && Q == QQ && B == BB) return instance<KK, QQ, BB>(contig);
+    ESCOIN_TILED_VARIANTS(ESCOIN_PICK)
 #undef ESCOIN_PICK
     return nullptr;
 }
@@ -279,7 +317,11 @@ TiledKernel pick(int K, int Q, int B) {
 }  // namespace
 
 bool tiled_variant_exists(int K, int Q, int B) {
-    return (K == 2 || K == 4 || K == 8 || K == 16) && (Q == 1 || Q == 2) && (B == 4 || B == 8);
+#define ESCOIN_HAS(KK, QQ, BB) \
+    if (K == KK && Q == QQ && B == BB) return true;
+    ESCOIN_TILED_VARIANTS(ESCOIN_HAS)
+#undef ESCOIN_HAS
+    return false;
 }
 
 }  // namespace escoin
@@ -300,16 +342,17 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     if (h.C != d.C || h.H != d.H || h.W != d.W || h.M != d.M || h.R != d.R || h.S != d.S ||
         h.stride != d.stride || h.pad != d.pad || h.E != d.E || h.F != d.F)
         return ESCOIN_EINVAL;
-    TiledKernel kern = pick(h.K, h.Q, h.B);
+    TiledKernel kern = pick(h.K, h.Q, h.B, h.NB == 1);
     if (!kern) return ESCOIN_EINVAL;
     const int threads = 64 * h.WQ * h.WM;
-    if (threads > 512 || threads <= 0) return ESCOIN_EINVAL;
+    if (threads > 1024 || threads <= 0) return ESCOIN_EINVAL;
     // the kernel's index arithmetic relies on these plan invariants
     if (h.P4 % 4 || h.plane_stride % 4 || h.P4 > h.plane_stride || h.NB < 1 || h.CC < 1 ||
-        h.WQ * 64 * h.Q * 4 < h.NB * h.P4 || h.tail_floats % 4 || h.rec_buf_bytes % 16 ||
-        h.buf_floats != h.n_slots * h.CC * h.NB * h.plane_stride ||
+        h.WQ < 1 || h.WM < 1 || h.tail_floats % 4 || h.rec_buf_bytes % 16 || h.front < 4 ||
+        h.n_phases < 1 || h.n_phases > kMaxPhases ||
+        h.buf_floats != h.n_phases * h.CC * h.NB * h.plane_stride ||
         (long long)h.n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads ||
-        h.rec_buf_bytes > kMaxRecLoadsPerThread * threads * 16 ||
+        (long long)h.buf_floats * 4 >= (1 << 24) ||
         h.lds_bytes != (2 * h.buf_floats + h.tail_floats) * 4 + 2 * h.rec_buf_bytes)
         return ESCOIN_EINVAL;
 
@@ -317,6 +360,7 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     TiledArgs a;
     a.in = d_in; a.out = d_out; a.bias = d_bias;
     a.items = (const StageItem*)(base + h.off_items);
+    a.lanes = (const LaneSlot*)(base + h.off_lanes);
     a.dst_lut = (const int32_t*)(base + h.off_dst_lut);
     a.perm = (const int32_t*)(base + h.off_perm);
     a.blk = (const uint32_t*)(base + h.off_blk);

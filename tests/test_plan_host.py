@@ -17,9 +17,9 @@ CASES = [
     ((2, 6, 17, 19, 5, 3, 3, 2, 1, 0.6), dict(K=4, TH=4, WM=2)),
     ((2, 9, 12, 13, 10, 1, 1, 1, 0, 0.6), dict(K=8, CC=4)),
     ((1, 3, 23, 19, 3, 7, 7, 2, 3, 0.5), dict(K=2, TH=3)),
-    ((2, 3, 10, 12, 4, 2, 3, 3, 2, 0.4), dict(K=4, Q=2, B=8)),
-    ((5, 8, 7, 7, 12, 3, 3, 1, 1, 0.8), dict(K=16, NB=3, WM=1)),
-    ((2, 3, 30, 37, 4, 3, 3, 1, 0, 0.5), dict(TH=9, Q=2)),
+    ((2, 3, 10, 12, 4, 2, 3, 3, 2, 0.4), dict(K=4, Q=2, B=4)),
+    ((5, 8, 7, 7, 12, 3, 3, 1, 1, 0.8), dict(K=8, NB=3, WM=1)),
+    ((2, 3, 30, 37, 4, 3, 3, 1, 0, 0.5), dict(TH=6, Q=2)),
 ]
 
 
@@ -70,7 +70,7 @@ def test_rows_are_dealt_out_balanced():
     perm = plan[h["off_perm"]:h["off_perm"] + 4 * bins * h["K"]].view(np.int32).reshape(bins, h["K"])
     nnz_row = np.diff(L.rowptr)
     load = np.array([nnz_row[p[p >= 0]].sum() for p in perm])
-    assert load.max() <= 1.35 * load.mean()        # rows alone: max/mean = 5.0
+    assert load.max() <= 1.45 * load.mean()        # rows alone: max/mean = 5.0
     assert nnz_row.max() / nnz_row.mean() > 4.5
 
 
