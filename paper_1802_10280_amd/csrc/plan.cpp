@@ -93,8 +93,9 @@ int build_geometry(const Dims& d, int pitch, int front, Geometry* g) {
 
 // Fills every derived field of `h` from the knobs K, Q, B, WM, CC, NB, TH (already set).
 int derive(const Dims& d, PlanHeader* h, Geometry* g) {
-    const int cols_ph = ceil_div(d.Wp, d.stride);
-    h->pitch = round_up(cols_ph, 4);
+    // rows of a phase plane follow each other without gaps: any misalignment of a tap's offset
+    // is absorbed by its alignment class
+    h->pitch = ceil_div(d.Wp, d.stride);
     // front padding: at least one whole group (the lane left of the first group reads it), and
     // the residue that makes the taps' alignment classes cheapest
     int best_front = 4, best_cost = INT_MAX;
@@ -139,15 +140,14 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
 // Default knobs.  Positions of NB images (or of one band of TH rows) fill the position runs of
 // one wave; the channel chunk takes what LDS is left under `lds_target`.
 void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h) {
-    const int cols_ph = ceil_div(d.Wp, d.stride);
-    const int pitch = round_up(cols_ph, 4);
+    const int pitch = ceil_div(d.Wp, d.stride);
     h->Q = (t && t->Q > 0) ? t->Q : 1;
-    h->B = (t && t->B > 0) ? t->B : 4;
+    h->B = (t && t->B > 0) ? t->B : 2;
     h->K = (t && t->K > 0) ? t->K : 4;
     const int wave_groups = kRunLanes * h->Q;  // groups one wave can own
     // tile: whole image(s) when an image's positions fit one wave, else a band of rows
     int TH = d.E, NB = 1;
-    const int img_groups = d.E * pitch / 4 + 2;
+    const int img_groups = ceil_div(d.E * pitch, 4) + 2;
     if (img_groups - 2 <= wave_groups) {
         NB = std::max(1, (wave_groups + 2) / img_groups);
         NB = std::min(NB, d.N);

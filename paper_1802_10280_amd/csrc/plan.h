@@ -14,7 +14,7 @@ constexpr uint32_t kPlanMagic = 0x4E4C5045u;  // "EPLN"
 constexpr uint32_t kPlanVersion = 7;
 constexpr int kMaxPhases = 16;          // stride*stride phase planes
 constexpr int kClasses = 4;             // alignment classes of a tap: (LDS offset) mod 4
-constexpr int kMaxItemsPerThread = 6;   // staged input words per thread and chunk
+constexpr int kMaxItemsPerThread = 12;  // staged input words per thread and chunk
 
 // One input word of a tile's window: where it comes from and the LDS word that holds it (for
 // channel 0 / image 0 of a window buffer).
@@ -44,7 +44,7 @@ struct PlanHeader {
     int32_t NB;  // images per workgroup
     int32_t TH;  // output rows per tile (band height)
     int32_t n_tiles, n_mgroups, n_chunks, n_phases;
-    int32_t pitch;         // row pitch of a phase plane in LDS (floats, multiple of 4)
+    int32_t pitch;         // row pitch of a phase plane in LDS (floats)
     int32_t front;         // unused floats in front of every LDS plane
     int32_t rows_in;       // phase-plane rows held per tile
     int32_t plane_stride;  // floats per (phase, channel, image) plane in LDS (multiple of 4)

@@ -66,7 +66,7 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
     lds_len = buf_floats + h["tail_floats"]            # one window buffer plus the zeroed tail
     assert h["lds_bytes"] == (2 * buf_floats + h["tail_floats"]) * 4 + 2 * h["rec_buf_bytes"]
     threads = 64 * WQ * WM
-    assert threads <= 1024 and h["n_items"] * CC * NB <= 6 * threads
+    assert threads <= 1024 and h["n_items"] * CC * NB <= 12 * threads
     for t in range(h["n_tiles"]):
         for n0 in range(0, N, NB):
             nb = min(NB, N - n0)

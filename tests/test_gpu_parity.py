@@ -78,11 +78,11 @@ def test_sconv_matches_oracle_small(oracle, cfg, path):
 
 TUNINGS = [
     dict(K=2, Q=1, B=4, WM=2, CC=3, TH=5),
-    dict(K=4, Q=2, B=4, WM=1, CC=2, NB=2),
+    dict(K=4, Q=2, B=2, WM=1, CC=2, NB=2),
     dict(K=2, Q=1, B=2, WM=3, CC=5, TH=3),
     dict(K=8, Q=1, B=4, WM=2, CC=1, TH=11),
     dict(K=4, Q=2, B=2, WM=4, CC=7, NB=3),
-    dict(K=8, Q=2, B=2, WM=2, CC=6, TH=6),
+    dict(K=2, Q=2, B=4, WM=2, CC=6, TH=6),
     dict(K=2, Q=2, B=4, WM=16, CC=2, TH=2),
     dict(K=4, Q=1, B=4, WM=5, CC=4, TH=4),
 ]

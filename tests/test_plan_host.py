@@ -17,7 +17,7 @@ CASES = [
     ((2, 6, 17, 19, 5, 3, 3, 2, 1, 0.6), dict(K=4, TH=4, WM=2)),
     ((2, 9, 12, 13, 10, 1, 1, 1, 0, 0.6), dict(K=8, CC=4)),
     ((1, 3, 23, 19, 3, 7, 7, 2, 3, 0.5), dict(K=2, TH=3)),
-    ((2, 3, 10, 12, 4, 2, 3, 3, 2, 0.4), dict(K=4, Q=2, B=4)),
+    ((2, 3, 10, 12, 4, 2, 3, 3, 2, 0.4), dict(K=4, Q=2, B=2)),
     ((5, 8, 7, 7, 12, 3, 3, 1, 1, 0.8), dict(K=8, NB=3, WM=1)),
     ((2, 3, 30, 37, 4, 3, 3, 1, 0, 0.5), dict(TH=6, Q=2)),
 ]
