@@ -27,6 +27,7 @@
 #include <limits.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <numeric>
 #include <vector>
@@ -137,35 +138,82 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
     return ESCOIN_OK;
 }
 
-// Default knobs.  Positions of NB images (or of one band of TH rows) fill the position runs of
-// one wave; the channel chunk takes what LDS is left under `lds_target`.
+// Default knobs.  Every (K, Q) pair and tile shape is scored by how well it would fill the
+// machine: the share of a wave's lanes that own output positions, times the share of the 256
+// compute units that get a workgroup in the last round of workgroups, with a bonus for two
+// position runs per lane (records and addresses are shared by both) and for four rows per wave.
+// The channel chunk then takes the LDS that is left.
 void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h) {
+    static const int kPairs[4][2] = {{4, 2}, {2, 2}, {4, 1}, {2, 1}};
     const int pitch = ceil_div(d.Wp, d.stride);
-    h->Q = (t && t->Q > 0) ? t->Q : 1;
-    h->B = (t && t->B > 0) ? t->B : 2;
-    h->K = (t && t->K > 0) ? t->K : 4;
-    const int wave_groups = kRunLanes * h->Q;  // groups one wave can own
-    // tile: whole image(s) when an image's positions fit one wave, else a band of rows
-    int TH = d.E, NB = 1;
-    const int img_groups = ceil_div(d.E * pitch, 4) + 2;
-    if (img_groups - 2 <= wave_groups) {
-        NB = std::max(1, (wave_groups + 2) / img_groups);
-        NB = std::min(NB, d.N);
-    } else {
-        TH = std::max(1, wave_groups * 4 / pitch);
-        TH = ceil_div(d.E, ceil_div(d.E, TH));  // even out the bands
+    const int img_groups = ceil_div(d.E * pitch, 4);
+    int bestK = 2, bestQ = 1, bestTH = d.E, bestNB = 1, bestWM = 1;
+    double best_score = -1.0;
+    for (int i = 0; i < 4 * 3; ++i) {
+        const int K = kPairs[i / 3][0], Q = kPairs[i / 3][1];
+        if (t && t->K > 0 && t->K != K) continue;
+        if (t && t->Q > 0 && t->Q != Q) continue;
+        if (!(t && t->Q > 0) && Q == 2 && d.stride > 1) continue;  // several phase planes: LDS goes to CC
+        // fewer waves per workgroup give more workgroups (small batches need that) but every
+        // wave then stages a larger share of the window
+        int WM = 16 >> (i % 3);
+        if (t && t->WM > 0) {
+            if (i % 3) continue;
+            WM = t->WM;
+        } else if (WM > ceil_div(d.M, K)) {
+            if (WM / 2 >= ceil_div(d.M, K)) continue;
+            WM = ceil_div(d.M, K);
+        }
+        const double share = 0.6 + 0.4 * WM / 16.0;
+        const int wave_groups = kRunLanes * Q;  // groups one wave can own
+        const int mgroups = ceil_div(d.M, K * WM);
+        auto consider = [&](int TH, int NB, int groups_per_wave) {
+            const long long wgs = (long long)ceil_div(d.E, TH) * ceil_div(d.N, NB) * mgroups;
+            const double lane_eff = (double)groups_per_wave / (64.0 * Q);
+            const double fill = (double)wgs / (double)(ceil_div((int)std::min<long long>(wgs, 1 << 20), 256) * 256);
+            // channels per chunk the staging registers allow: short chunks mean many barriers
+            // and much padding of the record batches
+            const int rows = std::min(d.H, (TH - 1) * d.stride + d.R);
+            const int runs = std::max(1, ceil_div(NB * (ceil_div(TH * pitch, 4) + 2) - 2, kRunLanes));
+            const double cc_est = (double)kMaxItemsPerThread * 64 * WM * ceil_div(runs, Q) /
+                                  ((double)rows * d.W * NB);
+            const double chunk = std::sqrt(std::min(1.0, std::min((double)d.C, cc_est) / 16.0));
+            const double score =
+                lane_eff * fill * share * chunk * (Q == 2 ? 1.2 : 1.0) * (K == 4 ? 1.1 : 1.0);
+            if (score > best_score) {
+                best_score = score; bestK = K; bestQ = Q; bestTH = TH; bestNB = NB; bestWM = WM;
+            }
+        };
+        if (img_groups <= wave_groups) {  // whole images: NB of them per workgroup
+            const int nb_max = std::max(1, std::min(d.N, (wave_groups + 2) / (img_groups + 2)));
+            for (int NB = nb_max; NB >= 1; --NB) {
+                if (ceil_div(NB * (img_groups + 2) - 2, kRunLanes) < Q) break;  // idle position run
+                consider(d.E, NB, NB * img_groups);
+            }
+        } else {  // a band of rows of one image
+            int TH = std::max(1, wave_groups * 4 / pitch);
+            TH = ceil_div(d.E, ceil_div(d.E, TH));  // even out the bands
+            consider(TH, 1, std::min(wave_groups, ceil_div(TH * pitch, 4)));
+        }
     }
-    h->TH = (t && t->TH > 0) ? t->TH : TH;
-    h->NB = (t && t->NB > 0) ? t->NB : ((t && t->TH > 0 && t->TH < d.E) ? 1 : NB);
-    int WM = std::min(16, ceil_div(d.M, h->K));
-    h->WM = (t && t->WM > 0) ? t->WM : WM;
+    if (best_score < 0) {  // the caller fixed a (K, Q) outside the table
+        bestK = (t && t->K > 0) ? t->K : 2;
+        bestQ = (t && t->Q > 0) ? t->Q : 1;
+        bestWM = std::min(16, ceil_div(d.M, bestK));
+    }
+    h->K = bestK;
+    h->Q = bestQ;
+    h->B = (t && t->B > 0) ? t->B : 2;
+    h->TH = (t && t->TH > 0) ? t->TH : bestTH;
+    h->NB = (t && t->NB > 0) ? t->NB : ((t && t->TH > 0 && t->TH < d.E) ? 1 : bestNB);
+    h->WM = (t && t->WM > 0) ? t->WM : bestWM;
     if (t && t->CC > 0) {
         h->CC = t->CC;
     } else {
         Geometry g;
         PlanHeader probe = *h;
         probe.CC = 1;
-        const int lds_target = 96 * 1024;
+        const int lds_target = 100 * 1024;
         if (derive(d, &probe, &g) == ESCOIN_OK) {
             const int per_c = 2 * probe.n_phases * probe.NB * probe.plane_stride * 4;
             h->CC = std::max(1, std::min(d.C, lds_target / per_c));
