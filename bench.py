@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--cpu-images", type=int, default=0,
                     help="images per layer for the oracle sample (0 = auto, about 10-30 s)")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: a few launches of a plain copy of known size "
+                         "(pad_in with pad 0) and of every layer's kernels, nothing timed")
     return ap.parse_args()
 
 
@@ -76,6 +79,19 @@ def main():
     def step():
         for r in runners:
             r.run()
+
+    if args.traffic_probe:
+        # the copy moves exactly 2 * 64 MiB: it calibrates what FETCH_SIZE / WRITE_SIZE read
+        n = 16 * 1024 * 1024
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        d = esc.make_desc(1, 1, 4096, 4096, 1, 1, 1, 1, 0)
+        for _ in range(3):
+            esc.escoin_pad_in(d, src, dst)
+            step()
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": "done", "copy_bytes_read": 4 * n, "copy_bytes_written": 4 * n}))
+        return
 
     for _ in range(args.warmup):
         step()
