@@ -119,7 +119,7 @@ int escoin_sconv_forward(const escoin_conv_desc *desc, const int32_t *d_rowptr,
 /* Tiling knobs; a zero field means "choose for me".  Out-of-range combinations make the plan
  * calls return ESCOIN_EINVAL / ESCOIN_ERANGE (e.g. a window that does not fit LDS). */
 typedef struct escoin_sconv_tuning {
-    int32_t K;  /* output channels accumulated per wave: 2, 4 or 8                  */
+    int32_t K;  /* output channels accumulated per wave: 1, 2, 4 or 8               */
     int32_t Q;  /* 16-byte position groups per lane, 1 or 2                         */
     int32_t B;  /* nonzeros per record batch, 2 or 4 (not every K/Q/B mix exists)   */
     int32_t WM; /* waves per workgroup along the output-channel axis                */

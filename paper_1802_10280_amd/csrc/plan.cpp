@@ -138,11 +138,12 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
     return ESCOIN_OK;
 }
 
-// Default knobs.  Every (K, Q) pair and tile shape is scored by how well it would fill the
-// machine: the share of a wave's lanes that own output positions, times the share of the 256
-// compute units that get a workgroup in the last round of workgroups, with a bonus for two
-// position runs per lane (records and addresses are shared by both) and for four rows per wave.
-// The channel chunk then takes the LDS that is left.
+// Default knobs.  Every (K, Q, WM) choice and tile shape gets a relative cost: rounds of
+// workgroups over the 256 compute units, times the work of one wave (K rows; two position runs
+// per lane cost 1.75x one), with penalties for leaving compute units idle, for workgroups
+// with few waves (each wave then stages a larger share of the window) and for short channel
+// chunks.  The cheapest wins; ties go to more rows per wave.  The channel chunk then takes the
+// LDS that is left.
 void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h) {
     static const int kPairs[4][2] = {{4, 2}, {2, 2}, {4, 1}, {2, 1}};
     const int pitch = ceil_div(d.Wp, d.stride);
@@ -164,13 +165,14 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
             if (WM / 2 >= ceil_div(d.M, K)) continue;
             WM = ceil_div(d.M, K);
         }
-        const double share = 0.6 + 0.4 * WM / 16.0;
+        const double share = 0.5 + 0.5 * WM / 16.0;
         const int wave_groups = kRunLanes * Q;  // groups one wave can own
         const int mgroups = ceil_div(d.M, K * WM);
         auto consider = [&](int TH, int NB, int groups_per_wave) {
             const long long wgs = (long long)ceil_div(d.E, TH) * ceil_div(d.N, NB) * mgroups;
-            const double lane_eff = (double)groups_per_wave / (64.0 * Q);
-            const double fill = (double)wgs / (double)(ceil_div((int)std::min<long long>(wgs, 1 << 20), 256) * 256);
+            (void)groups_per_wave;
+            const double rounds = (double)ceil_div((int)std::min<long long>(wgs, 1 << 20), 256);
+            const double fill = std::sqrt(std::min(1.0, (double)wgs / 256.0));
             // channels per chunk the staging registers allow: short chunks mean many barriers
             // and much padding of the record batches
             const int rows = std::min(d.H, (TH - 1) * d.stride + d.R);
@@ -178,8 +180,10 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
             const double cc_est = (double)kMaxItemsPerThread * 64 * WM * ceil_div(runs, Q) /
                                   ((double)rows * d.W * NB);
             const double chunk = std::sqrt(std::min(1.0, std::min((double)d.C, cc_est) / 16.0));
-            const double score =
-                lane_eff * fill * share * chunk * (Q == 2 ? 1.2 : 1.0) * (K == 4 ? 1.1 : 1.0);
+            // 0.6: the per-workgroup fixed work (set-up, first fetch, store) in units of one row
+            const double cost =
+                rounds * (K * (Q == 2 ? (NB == 1 ? 1.75 : 1.9) : 1.0) + 0.6) / (fill * share * chunk);
+            const double score = 1.0 / cost * (1.0 + 1e-3 * K);
             if (score > best_score) {
                 best_score = score; bestK = K; bestQ = Q; bestTH = TH; bestNB = NB; bestWM = WM;
             }

@@ -298,7 +298,7 @@ typedef void (*TiledKernel)(const TiledArgs);
 
 // (K, Q, B) instantiations: the ones that fit 128 VGPRs (four waves per SIMD) without spilling.
 #define ESCOIN_TILED_VARIANTS(X) \
-    X(2, 1, 2) X(2, 1, 4) X(2, 2, 2) X(2, 2, 4) X(4, 1, 2) X(4, 1, 4) X(4, 2, 2) X(8, 1, 2) X(8, 1, 4)
+    X(1, 1, 2) X(1, 2, 2) X(2, 1, 2) X(2, 1, 4) X(2, 2, 2) X(2, 2, 4) X(4, 1, 2) X(4, 1, 4) X(4, 2, 2) X(8, 1, 2) X(8, 1, 4)
 
 template <int K, int Q, int B>
 TiledKernel instance(bool contig) {
