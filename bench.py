@@ -90,7 +90,13 @@ def main():
             esc.escoin_pad_in(d, src, dst)
             step()
         torch.cuda.synchronize()
-        print(json.dumps({"traffic_probe": "done", "copy_bytes_read": 4 * n, "copy_bytes_written": 4 * n}))
+        print(json.dumps({"traffic_probe": "done", "copy_bytes_read": 4 * n, "copy_bytes_written": 4 * n,
+                          "launch_order": ["copy"] + [L.spec.name for L in layers], "rounds": 3,
+                          "layers": [{"layer": L.spec.name, "N": L.spec.N, "nnz": L.nnz,
+                                      "kernel": r.sconv_kernel_name(),
+                                      "plan": {k: r.plan_info[k] for k in ("K", "Q", "B", "WM", "CC", "NB", "TH")}
+                                      if r.path == "tiled" else None}
+                                     for L, r in zip(layers, runners)]}))
         return
 
     for _ in range(args.warmup):

@@ -72,5 +72,19 @@ class LayerRunner:
         return self.d_out
 
     def measured_traffic(self):
-        """HBM bytes per launch from rocprofv3 counters, when a profile has been recorded."""
+        """HBM bytes one launch of this layer's sconv kernel moved, read plus written, as the
+        rocprofv3 FETCH_SIZE / WRITE_SIZE counters recorded it (hbm_traffic.json beside this
+        file, written from the counter runs whose summary sits under profiles/).  None when no
+        record matches this layer, batch size and tiling exactly."""
+        import json, os
+        if self.path != "tiled":
+            return None
+        table = os.path.join(os.path.dirname(os.path.abspath(__file__)), "hbm_traffic.json")
+        if not os.path.exists(table):
+            return None
+        h, s = self.plan_info, self.layer.spec
+        for rec in json.load(open(table))["records"]:
+            if (rec["layer"] == s.name and rec["N"] == s.N and rec["nnz"] == self.layer.nnz
+                    and all(rec["plan"][k] == h[k] for k in rec["plan"])):
+                return rec["read_bytes"] + rec["written_bytes"]
         return None
