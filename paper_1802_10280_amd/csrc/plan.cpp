@@ -61,6 +61,44 @@ struct Geometry {
 // 3) one word from the previous lane.
 inline int class_cost(int c) { return c == 0 ? 0 : (c == 2 ? 2 : 1); }
 
+// Front padding of a phase plane: at least one whole group (the lane left of the first group
+// reads it), and the residue that makes the taps' alignment classes cheapest.
+int choose_front(const Dims& d, int pitch) {
+    int best_front = 4, best_cost = INT_MAX;
+    for (int front = 4; front < 8; ++front) {
+        int cost = 0;
+        for (int r = 0; r < d.R; ++r)
+            for (int s = 0; s < d.S; ++s)
+                cost += class_cost((front + (r / d.stride) * pitch + s / d.stride) % 4);
+        if (cost < best_cost) {
+            best_cost = cost;
+            best_front = front;
+        }
+    }
+    return best_front;
+}
+
+inline int plane_stride_of(int front, int rows_in, int pitch) { return round_up(front + rows_in * pitch + 4, 4); }
+
+// Lane layout of a tile that holds NB images.  Each image takes groups_per_image + 2 entries
+// in a row (its groups and one lending group on either side).  A 16-byte LDS read is
+// conflict-free when the lanes' group numbers (word address / 4) advance by one per lane
+// modulo the 16 groups the 64 banks hold, so image n starts at the first free entry whose index
+// is congruent to its first group number; the entries skipped in between stay idle.
+// Returns the entry index of image n's first (lending) group; n == NB gives the total count.
+int image_first_entry(int n, int groups_per_image, int plane_stride) {
+    int at = 0;  // image 0: its group -1 sits at entry 0, so entry index = group number + 1 (mod 16)
+    for (int i = 1; i <= n; ++i) {
+        const int free_at = at + groups_per_image + 2;
+        const int want = (int)(((long long)i * (plane_stride / 4)) % 16);
+        at = free_at + ((want - free_at) % 16 + 16) % 16;
+    }
+    return at;
+}
+inline int lane_entries(int NB, int groups_per_image, int plane_stride) {
+    return image_first_entry(NB - 1, groups_per_image, plane_stride) + groups_per_image + 2;
+}
+
 int build_geometry(const Dims& d, int pitch, int front, Geometry* g) {
     g->n_phases = 0;
     g->tap_phase.assign((size_t)d.R * d.S, -1);
@@ -97,31 +135,18 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
     // rows of a phase plane follow each other without gaps: any misalignment of a tap's offset
     // is absorbed by its alignment class
     h->pitch = ceil_div(d.Wp, d.stride);
-    // front padding: at least one whole group (the lane left of the first group reads it), and
-    // the residue that makes the taps' alignment classes cheapest
-    int best_front = 4, best_cost = INT_MAX;
-    for (int front = 4; front < 8; ++front) {
-        int cost = 0;
-        for (int r = 0; r < d.R; ++r)
-            for (int s = 0; s < d.S; ++s)
-                cost += class_cost((front + (r / d.stride) * h->pitch + s / d.stride) % 4);
-        if (cost < best_cost) {
-            best_cost = cost;
-            best_front = front;
-        }
-    }
-    h->front = best_front;
+    h->front = choose_front(d, h->pitch);
     int rc = build_geometry(d, h->pitch, h->front, g);
     if (rc != ESCOIN_OK) return rc;
     h->n_phases = g->n_phases;
     h->TH = std::min(h->TH, d.E);
     h->n_tiles = ceil_div(d.E, h->TH);
     h->rows_in = h->TH + (d.R - 1) / d.stride;
-    h->plane_stride = round_up(h->front + h->rows_in * h->pitch + 4, 4);
+    h->plane_stride = plane_stride_of(h->front, h->rows_in, h->pitch);
     h->P4 = round_up(h->TH * h->pitch, 4);
     // lanes: per image the groups -1 .. P4/4 (one lending group on either side); a run of 64
     // lanes owns the outputs of its 62 inner lanes, so consecutive runs overlap by two entries
-    const int entries = h->NB * (h->P4 / 4 + 2);
+    const int entries = lane_entries(h->NB, h->P4 / 4, h->plane_stride);
     const int runs = std::max(1, ceil_div(entries - 2, kRunLanes));
     h->WQ = ceil_div(runs, h->Q);
     h->CC = std::min(h->CC, d.C);
@@ -138,66 +163,81 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
     return ESCOIN_OK;
 }
 
-// Default knobs.  Every (K, Q, WM) choice and tile shape gets a relative cost: rounds of
-// workgroups over the 256 compute units, times the work of one wave (K rows; two position runs
-// per lane cost 1.75x one), with penalties for leaving compute units idle, for workgroups
-// with few waves (each wave then stages a larger share of the window) and for short channel
-// chunks.  The cheapest wins; ties go to more rows per wave.  The channel chunk then takes the
-// LDS that is left.
+// Default knobs.  Every (K, Q, WM) choice and tile shape gets a relative cost, in units of the
+// time one wave needs for one filter row: rounds of workgroups over the compute units, times
+// a fixed part (set-up, first fetch, store) plus the K rows of one wave.  Two position runs
+// per lane cost about 1.75x one; a wave runs faster when fewer waves share its SIMD; short
+// channel chunks mean many barriers and much padding of the record batches; workgroups of few
+// waves stage a larger share of the window per wave.  The constants were fitted to measured
+// sweeps over the layer shapes of the bundled workloads.  The cheapest wins; ties go to more
+// rows per wave.  The channel chunk then takes the LDS that is left.
 void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h) {
-    static const int kPairs[4][2] = {{4, 2}, {2, 2}, {4, 1}, {2, 1}};
+    // the last two are searched only when the caller asks for that K or Q
+    static const int kPairs[7][2] = {{4, 2}, {2, 2}, {4, 1}, {2, 1}, {1, 1}, {1, 2}, {8, 1}};
     const int pitch = ceil_div(d.Wp, d.stride);
     const int img_groups = ceil_div(d.E * pitch, 4);
     int bestK = 2, bestQ = 1, bestTH = d.E, bestNB = 1, bestWM = 1;
     double best_score = -1.0;
-    for (int i = 0; i < 4 * 3; ++i) {
-        const int K = kPairs[i / 3][0], Q = kPairs[i / 3][1];
+    static const int kWaves[5] = {16, 12, 8, 6, 4};
+    static const double kStageShare[5] = {1.0, 1.02, 1.08, 1.2, 1.4};
+    for (int i = 0; i < 7 * 5; ++i) {
+        const int K = kPairs[i / 5][0], Q = kPairs[i / 5][1];
         if (t && t->K > 0 && t->K != K) continue;
         if (t && t->Q > 0 && t->Q != Q) continue;
+        if (i / 5 == 5 && !(t && t->K == 1 && t->Q == 2)) continue;
+        if (i / 5 == 6 && !(t && t->K == 8)) continue;
         if (!(t && t->Q > 0) && Q == 2 && d.stride > 1) continue;  // several phase planes: LDS goes to CC
         // fewer waves per workgroup give more workgroups (small batches need that) but every
         // wave then stages a larger share of the window
-        int WM = 16 >> (i % 3);
+        int WM = kWaves[i % 5];
+        double stage_share = kStageShare[i % 5];
         if (t && t->WM > 0) {
-            if (i % 3) continue;
+            if (i % 5) continue;
             WM = t->WM;
+            stage_share = 1.0;
         } else if (WM > ceil_div(d.M, K)) {
-            if (WM / 2 >= ceil_div(d.M, K)) continue;
+            if (i % 5 + 1 < 5 && kWaves[i % 5 + 1] >= ceil_div(d.M, K)) continue;
             WM = ceil_div(d.M, K);
         }
-        const double share = 0.5 + 0.5 * WM / 16.0;
         const int wave_groups = kRunLanes * Q;  // groups one wave can own
         const int mgroups = ceil_div(d.M, K * WM);
-        auto consider = [&](int TH, int NB, int groups_per_wave) {
+        auto rows_lds = [&](int TH) { return TH + (d.R - 1) / d.stride; };
+        auto consider = [&](int TH, int NB) {
             const long long wgs = (long long)ceil_div(d.E, TH) * ceil_div(d.N, NB) * mgroups;
-            (void)groups_per_wave;
-            const double rounds = (double)ceil_div((int)std::min<long long>(wgs, 1 << 20), 256);
-            const double fill = std::sqrt(std::min(1.0, (double)wgs / 256.0));
-            // channels per chunk the staging registers allow: short chunks mean many barriers
-            // and much padding of the record batches
+            // the launch deals the workgroups out evenly over the 8 XCDs of 32 compute units
+            const double rounds =
+                (double)ceil_div(ceil_div((int)std::min<long long>(wgs, 1 << 20), 8), 32);
+            // channels per chunk the staging registers allow
             const int rows = std::min(d.H, (TH - 1) * d.stride + d.R);
-            const int runs = std::max(1, ceil_div(NB * (ceil_div(TH * pitch, 4) + 2) - 2, kRunLanes));
-            const double cc_est = (double)kMaxItemsPerThread * 64 * WM * ceil_div(runs, Q) /
-                                  ((double)rows * d.W * NB);
+            const int runs = std::max(
+                1, ceil_div(lane_entries(NB, ceil_div(TH * pitch, 4),
+                                         plane_stride_of(choose_front(d, pitch), rows_lds(TH), pitch)) - 2,
+                            kRunLanes));
+            const int WQ = ceil_div(runs, Q);
+            if (WQ * WM > 16) return;
+            const double cc_est = (double)kMaxItemsPerThread * 64 * WM * WQ / ((double)rows * d.W * NB);
             const double chunk = std::sqrt(std::min(1.0, std::min((double)d.C, cc_est) / 16.0));
-            // 0.6: the per-workgroup fixed work (set-up, first fetch, store) in units of one row
-            const double cost =
-                rounds * (K * (Q == 2 ? (NB == 1 ? 1.75 : 1.9) : 1.0) + 0.6) / (fill * share * chunk);
+            const int per_simd = ceil_div(WM * WQ, 4);
+            const double crowd = per_simd >= 4 ? 1.0 : (per_simd == 3 ? 0.9 : 0.8);
+            const double row_cost = Q == 2 ? (NB == 1 ? 1.75 : 1.9) : 1.0;
+            const double cost = rounds * (0.6 + K * row_cost * crowd / chunk) * stage_share;
             const double score = 1.0 / cost * (1.0 + 1e-3 * K);
             if (score > best_score) {
                 best_score = score; bestK = K; bestQ = Q; bestTH = TH; bestNB = NB; bestWM = WM;
             }
         };
         if (img_groups <= wave_groups) {  // whole images: NB of them per workgroup
-            const int nb_max = std::max(1, std::min(d.N, (wave_groups + 2) / (img_groups + 2)));
+            const int ps = plane_stride_of(choose_front(d, pitch), d.E + (d.R - 1) / d.stride, pitch);
+            int nb_max = 1;
+            while (nb_max < d.N && lane_entries(nb_max + 1, img_groups, ps) - 2 <= wave_groups) ++nb_max;
             for (int NB = nb_max; NB >= 1; --NB) {
-                if (ceil_div(NB * (img_groups + 2) - 2, kRunLanes) < Q) break;  // idle position run
-                consider(d.E, NB, NB * img_groups);
+                if (ceil_div(lane_entries(NB, img_groups, ps) - 2, kRunLanes) < Q) break;  // idle position run
+                consider(d.E, NB);
             }
         } else {  // a band of rows of one image
             int TH = std::max(1, wave_groups * 4 / pitch);
             TH = ceil_div(d.E, ceil_div(d.E, TH));  // even out the bands
-            consider(TH, 1, std::min(wave_groups, ceil_div(TH * pitch, 4)));
+            consider(TH, 1);
         }
     }
     if (best_score < 0) {  // the caller fixed a (K, Q) outside the table
@@ -316,7 +356,14 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     // ---- lanes of every position run
     const int gpi = h.P4 / 4;
     std::vector<LaneSlot> entries;
-    for (int nl = 0; nl < h.NB; ++nl)
+    for (int nl = 0; nl < h.NB; ++nl) {
+        const size_t first = (size_t)image_first_entry(nl, gpi, h.plane_stride);
+        while (entries.size() < first) {  // idle entries keep walking through the banks
+            LaneSlot e = entries.back();
+            e.base_word += 4;
+            e.pos0 = -1;
+            entries.push_back(e);
+        }
         for (int gi = -1; gi <= gpi; ++gi) {
             LaneSlot e;
             e.base_word = nl * h.plane_stride + 4 * gi;
@@ -324,6 +371,7 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
             e.nloc = nl;
             entries.push_back(e);
         }
+    }
     const int runs = h.WQ * h.Q;
     std::vector<LaneSlot> lanes((size_t)runs * 64);
     for (int r = 0; r < runs; ++r)
@@ -333,8 +381,10 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
             if (e < entries.size()) {
                 s = entries[e];
                 if (l == 0 || l == 63) s.pos0 = -1;  // run ends only lend their group
-            } else {  // idle lane: shadow the first real group, own nothing
-                s = entries[1];
+            } else {  // idle lane: shadow an entry in the same banks (16 groups back), own nothing
+                long long idx = (long long)e;
+                while (idx >= (long long)entries.size()) idx -= 16;
+                s = entries[idx >= 0 ? (size_t)idx : e % entries.size()];
                 s.pos0 = -1;
             }
             lanes[(size_t)r * 64 + l] = s;

@@ -108,12 +108,17 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
     const int nthreads = blockDim.x;
 
     // Workgroup -> (input tile, output-channel group).  Consecutive workgroup ids land on
-    // different XCDs, so all channel groups of one input tile are given ids that are equal
-    // mod 8: they run on the same XCD and share the tile through its L2.
+    // different XCDs (id mod 8).  The n_in_tiles * n_mgroups jobs, ordered tile-major, are cut
+    // into 8 contiguous, equally long ranges, one per XCD: every XCD gets the same number of
+    // workgroups, and the channel groups of one input tile mostly run on one XCD, one after
+    // the other, sharing the tile through its L2.
     const int xcd = blockIdx.x & 7, slot_j = blockIdx.x >> 3;
-    const int mg = slot_j % a.n_mgroups;
-    const int t_in = (slot_j / a.n_mgroups) * 8 + xcd;
-    if (t_in >= a.n_in_tiles) return;  // whole workgroup leaves before any barrier
+    const int jobs = a.n_in_tiles * a.n_mgroups;
+    const int jq = jobs >> 3, jr = jobs & 7;
+    if (slot_j >= jq + (xcd < jr ? 1 : 0)) return;  // whole workgroup leaves before any barrier
+    const int job = xcd * jq + (xcd < jr ? xcd : jr) + slot_j;
+    const int t_in = job / a.n_mgroups;
+    const int mg = job - t_in * a.n_mgroups;
     const int tile = t_in % a.n_tiles;
     const int n0 = (t_in / a.n_tiles) * a.NB;
 
@@ -370,7 +375,7 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     a.WM = h.WM; a.WQ = h.WQ; a.CC = h.CC; a.NB = h.NB;
     a.n_tiles = h.n_tiles; a.n_mgroups = h.n_mgroups; a.n_chunks = h.n_chunks;
     const long long n_in_tiles = (long long)h.n_tiles * ((d.N + h.NB - 1) / h.NB);
-    const long long blocks = (n_in_tiles + 7) / 8 * 8 * h.n_mgroups;
+    const long long blocks = (n_in_tiles * h.n_mgroups + 7) / 8 * 8;
     if (blocks > 0x7FFFFFFFll) return ESCOIN_ERANGE;
     a.n_in_tiles = (int)n_in_tiles;
     a.plane_stride = h.plane_stride; a.P4 = h.P4; a.n_items = h.n_items;

@@ -20,6 +20,8 @@ CASES = [
     ((2, 3, 10, 12, 4, 2, 3, 3, 2, 0.4), dict(K=4, Q=2, B=2)),
     ((5, 8, 7, 7, 12, 3, 3, 1, 1, 0.8), dict(K=8, NB=3, WM=1)),
     ((2, 3, 30, 37, 4, 3, 3, 1, 0, 0.5), dict(TH=6, Q=2)),
+    ((7, 5, 7, 7, 6, 3, 3, 1, 1, 0.6), dict(K=2, NB=3)),          # idle lanes between images
+    ((6, 4, 13, 13, 5, 3, 3, 1, 1, 0.6), dict(K=2, Q=2, NB=2)),   # two runs, two images
 ]
 
 
@@ -72,6 +74,28 @@ def test_rows_are_dealt_out_balanced():
     load = np.array([nnz_row[p[p >= 0]].sum() for p in perm])
     assert load.max() <= 1.45 * load.mean()        # rows alone: max/mean = 5.0
     assert nnz_row.max() / nnz_row.mean() > 4.5
+
+
+@pytest.mark.parametrize("name,tune", [("R7", {}), ("R7", dict(NB=2)), ("A3b64", dict(Q=2, NB=2)),
+                                       ("G3", {}), ("R56s2", {})])
+def test_lanes_walk_through_the_lds_banks(name, tune):
+    """A 16-byte LDS read is conflict-free when the group numbers (word address / 4) of
+    consecutive lanes advance by one modulo 16, also across the boundary between two images
+    and for the lanes that own nothing."""
+    L = wl.make_layer(name, with_input=False)
+    d = esc.desc_of(L.spec)
+    st = esc.escoin_sconv_pack(d, L.rowptr, L.colidx)
+    plan = esc.escoin_sconv_plan_build(d, L.rowptr, st, L.value, esc.make_tuning(**tune))
+    h = esc.plan_header(plan)
+    runs = h["WQ"] * h["Q"]
+    lanes = plan[h["off_lanes"]:h["off_lanes"] + 12 * runs * 64].view(np.int32).reshape(runs, 64, 3)
+    assert np.all(lanes[:, :, 0] % 4 == 0)
+    group = lanes[:, :, 0] // 4
+    for r in range(runs):
+        assert len(set((group[r] - np.arange(64)) % 16)) == 1, (name, r)
+    assert lanes[:, :, 0].min() == -4 and lanes[:, :, 0].max() <= h["NB"] * h["plane_stride"]
+    owned = lanes[:, :, 1] >= 0
+    assert owned.sum() == h["NB"] * h["P4"] // 4                  # every group owned exactly once
 
 
 def test_plan_error_paths():
