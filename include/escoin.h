@@ -126,6 +126,8 @@ typedef struct escoin_sconv_tuning {
     int32_t CC; /* input channels staged per LDS chunk                              */
     int32_t NB; /* images per workgroup                                             */
     int32_t TH; /* output rows per tile                                             */
+    int32_t CS; /* workgroups sharing one output tile, each taking every CS-th      */
+                /* channel chunk and adding its partial sums with float atomics     */
 } escoin_sconv_tuning;
 
 /* Bytes the plan blob needs.  Host; rowptr / colidx_stretched as returned by
@@ -150,6 +152,13 @@ int escoin_sconv_plan_build(const escoin_conv_desc *desc, const int32_t *rowptr,
  *   d_in       device, N*C*H*W floats, UNPADDED
  *   d_out      device, N*M*E*F floats, overwritten
  * ESCOIN_EINVAL if the plan was built for another layer geometry.
+ *
+ * A plan with CS > 1 (chosen by default only when the batch is too small to give every compute
+ * unit a workgroup otherwise) splits the input channels of a tile over CS workgroups.  The call
+ * then enqueues three kernels instead of one: a zero fill of d_out, the convolution, whose
+ * workgroups add their partial sums with fp32 atomics (the order of those additions, and with
+ * it the last bits of the result, may differ from run to run), and, with ESCOIN_F_RELU, the
+ * clamp as a pass of its own.
  */
 int escoin_sconv_forward_tiled(const escoin_conv_desc *desc, const void *plan_host,
                                const void *d_plan, const float *d_in, float *d_out,

@@ -23,7 +23,7 @@ class escoin_conv_desc(ctypes.Structure):
 
 
 class escoin_sconv_tuning(ctypes.Structure):
-    _fields_ = [(k, ctypes.c_int32) for k in ("K", "Q", "B", "WM", "CC", "NB", "TH")]
+    _fields_ = [(k, ctypes.c_int32) for k in ("K", "Q", "B", "WM", "CC", "NB", "TH", "CS")]
 
 
 class EscoinError(RuntimeError):
@@ -205,7 +205,8 @@ PLAN_HEADER_FIELDS = (
      "rows_in", "plane_stride", "P4", "n_items", "buf_floats", "tail_floats", "rec_buf_bytes",
      "lds_bytes", "nnz", "n_records"],
     ["off_items", "off_lanes", "off_dst_lut", "off_perm", "off_blk", "off_seg", "off_rec",
-     "total_bytes"])
+     "total_bytes"],
+    ["CS"])
 
 
 def plan_header(plan: np.ndarray) -> dict:
@@ -215,4 +216,7 @@ def plan_header(plan: np.ndarray) -> dict:
     b = plan[n32 * 4:n32 * 4 + 8 * len(PLAN_HEADER_FIELDS[1])].view(np.uint64)
     h = {k: int(v) for k, v in zip(PLAN_HEADER_FIELDS[0], a)}
     h.update({k: int(v) for k, v in zip(PLAN_HEADER_FIELDS[1], b)})
+    n64 = len(PLAN_HEADER_FIELDS[1])
+    c = plan[n32 * 4 + 8 * n64:n32 * 4 + 8 * n64 + 4 * len(PLAN_HEADER_FIELDS[2])].view(np.int32)
+    h.update({k: int(v) for k, v in zip(PLAN_HEADER_FIELDS[2], c)})
     return h

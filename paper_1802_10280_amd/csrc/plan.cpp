@@ -78,6 +78,14 @@ int choose_front(const Dims& d, int pitch) {
     return best_front;
 }
 
+// Pitch of a phase plane.  Rows follow each other without gaps unless rounding the pitch up to
+// a multiple of 4 costs at most 7 % more positions: then every tap row has the same alignment
+// classes (three instead of four for a 3-wide filter, so longer record segments and fewer
+// lane shifts).
+inline int plane_pitch(const Dims& d) {
+    const int p = ceil_div(d.Wp, d.stride), p4 = round_up(p, 4);
+    return p4 * 100 <= p * 107 ? p4 : p;
+}
 inline int plane_stride_of(int front, int rows_in, int pitch) { return round_up(front + rows_in * pitch + 4, 4); }
 
 // Lane layout of a tile that holds NB images.  Each image takes groups_per_image + 2 entries
@@ -132,9 +140,7 @@ int build_geometry(const Dims& d, int pitch, int front, Geometry* g) {
 
 // Fills every derived field of `h` from the knobs K, Q, B, WM, CC, NB, TH (already set).
 int derive(const Dims& d, PlanHeader* h, Geometry* g) {
-    // rows of a phase plane follow each other without gaps: any misalignment of a tap's offset
-    // is absorbed by its alignment class
-    h->pitch = ceil_div(d.Wp, d.stride);
+    h->pitch = plane_pitch(d);
     h->front = choose_front(d, h->pitch);
     int rc = build_geometry(d, h->pitch, h->front, g);
     if (rc != ESCOIN_OK) return rc;
@@ -151,6 +157,7 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
     h->WQ = ceil_div(runs, h->Q);
     h->CC = std::min(h->CC, d.C);
     h->n_chunks = ceil_div(d.C, h->CC);
+    h->CS = std::max(1, std::min(h->CS, h->n_chunks));
     h->n_mgroups = ceil_div(d.M, h->K * h->WM);
     // two window buffers (the next chunk is fetched while the current one is consumed) plus a
     // zeroed tail that lanes past the last plane may read
@@ -174,7 +181,7 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
 void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h) {
     // the last two are searched only when the caller asks for that K or Q
     static const int kPairs[7][2] = {{4, 2}, {2, 2}, {4, 1}, {2, 1}, {1, 1}, {1, 2}, {8, 1}};
-    const int pitch = ceil_div(d.Wp, d.stride);
+    const int pitch = plane_pitch(d);
     const int img_groups = ceil_div(d.E * pitch, 4);
     int bestK = 2, bestQ = 1, bestTH = d.E, bestNB = 1, bestWM = 1;
     double best_score = -1.0;
@@ -266,6 +273,29 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
             h->CC = 1;
         }
     }
+}
+
+// Splitting the input channels of a tile over CS workgroups (which then add their partial sums
+// with atomics) pays only when the launch would otherwise leave most compute units without
+// a workgroup: small batches of small images.  Every workgroup keeps at least two chunks of
+// at least eight channels, and the chunk length is evened out so that all get the same number.
+void choose_split(const Dims& d, bool auto_cc, PlanHeader* h) {
+    Geometry g;
+    PlanHeader probe = *h;
+    probe.CS = 1;
+    h->CS = 1;
+    if (derive(d, &probe, &g) != ESCOIN_OK) return;
+    const long long wgs = (long long)probe.n_tiles * ceil_div(d.N, probe.NB) * probe.n_mgroups;
+    if (wgs > 96) return;
+    int cs = (int)std::min<long long>(192 / wgs, d.C / 16);
+    if (!auto_cc) cs = std::min(cs, probe.n_chunks / 2);
+    if (cs < 2) return;
+    if (auto_cc) {
+        const int chunks = cs * std::max(2, ceil_div(probe.n_chunks, cs));
+        h->CC = ceil_div(d.C, chunks);
+        h->CC = std::min(h->CC, probe.CC);
+    }
+    h->CS = cs;
 }
 
 struct RowNz {
@@ -533,7 +563,7 @@ int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_
     if (nnz > 0 && (!stretched || (out && !value))) return ESCOIN_EINVAL;
     if (tuning) {
         const int32_t* f = &tuning->K;
-        for (int i = 0; i < 7; ++i)
+        for (int i = 0; i < 8; ++i)
             if (f[i] < 0) return ESCOIN_EINVAL;
     }
 
@@ -549,7 +579,10 @@ int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_
     // record block all fit: first the channel chunk, then the band height / images per group.
     const bool auto_cc = !(tuning && tuning->CC > 0);
     const bool auto_tile = !(tuning && (tuning->TH > 0 || tuning->NB > 0));
+    const bool auto_cs = !(tuning && tuning->CS > 0);
+    h.CS = auto_cs ? 1 : tuning->CS;
     for (;;) {
+        if (auto_cs) choose_split(d, auto_cc, &h);
         rc = build_plan_once(d, rowptr, stretched, value, h, out, out_bytes, bytes);
         if (rc != ESCOIN_ERANGE) return rc;
         if (auto_cc && h.CC > 1) {

@@ -11,7 +11,7 @@
 namespace escoin {
 
 constexpr uint32_t kPlanMagic = 0x4E4C5045u;  // "EPLN"
-constexpr uint32_t kPlanVersion = 7;
+constexpr uint32_t kPlanVersion = 8;
 constexpr int kMaxPhases = 16;          // stride*stride phase planes
 constexpr int kClasses = 4;             // alignment classes of a tap: (LDS offset) mod 4
 constexpr int kMaxItemsPerThread = 12;  // staged input words per thread and chunk
@@ -65,7 +65,8 @@ struct PlanHeader {
                            // block, then batches per (row, class)
     uint64_t off_rec;      // {uint32 lds_byte_offset, float value} records, B per batch
     uint64_t total_bytes;
-    uint32_t reserved[8];
+    int32_t CS;  // workgroups that share an output tile; each takes every CS-th channel chunk
+    uint32_t reserved[7];
 };
 
 }  // namespace escoin

@@ -21,6 +21,8 @@
 //           with the optional bias + ReLU epilogue.
 // Consecutive lanes own consecutive positions (the data-to-thread mapping of Section 3.2), so
 // LDS reads are conflict-free and output stores are contiguous along w.
+#include <algorithm>
+
 #include "common.h"
 #include "plan.h"
 
@@ -41,7 +43,7 @@ struct TiledArgs {
     const uint32_t* seg;
     const uint32_t* rec;
     int N, C, HW, M, EF;
-    int WM, WQ, CC, NB;
+    int WM, WQ, CC, NB, CS;
     int n_tiles, n_mgroups, n_chunks, n_in_tiles;
     int plane_stride, P4, n_items, buf_floats, tail_floats, rec_buf_bytes;
     uint32_t flags;
@@ -107,18 +109,19 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
     const int wq = wave % a.WQ, wm = wave / a.WQ;
     const int nthreads = blockDim.x;
 
-    // Workgroup -> (input tile, output-channel group).  Consecutive workgroup ids land on
-    // different XCDs (id mod 8).  The n_in_tiles * n_mgroups jobs, ordered tile-major, are cut
-    // into 8 contiguous, equally long ranges, one per XCD: every XCD gets the same number of
-    // workgroups, and the channel groups of one input tile mostly run on one XCD, one after
+    // Workgroup -> (input tile, output-channel group, channel split).  Consecutive workgroup
+    // ids land on different XCDs (id mod 8).  The jobs, ordered tile-major, are cut into 8
+    // contiguous, equally long ranges, one per XCD: every XCD gets the same number of
+    // workgroups, and the workgroups that read one input tile mostly run on one XCD, one after
     // the other, sharing the tile through its L2.
     const int xcd = blockIdx.x & 7, slot_j = blockIdx.x >> 3;
-    const int jobs = a.n_in_tiles * a.n_mgroups;
+    const int jobs = a.n_in_tiles * a.n_mgroups * a.CS;
     const int jq = jobs >> 3, jr = jobs & 7;
     if (slot_j >= jq + (xcd < jr ? 1 : 0)) return;  // whole workgroup leaves before any barrier
     const int job = xcd * jq + (xcd < jr ? xcd : jr) + slot_j;
-    const int t_in = job / a.n_mgroups;
-    const int mg = job - t_in * a.n_mgroups;
+    const int cs = job % a.CS;
+    const int t_in = (job / a.CS) / a.n_mgroups;
+    const int mg = (job / a.CS) - t_in * a.n_mgroups;
     const int tile = t_in % a.n_tiles;
     const int n0 = (t_in / a.n_tiles) * a.NB;
 
@@ -193,12 +196,13 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
                 *(float*)(win + (st_key[j] & 0xFFFFFF)) = st_val[j];
     };
 
-    fetch(0, 0);
+    // This workgroup's chunks: cs, cs + CS, ... (all of them unless the channels are split).
+    fetch(cs, 0);
     // The frame of zeros never changes: clear the window buffers and the tail once; from here
     // on only words that hold input are rewritten, chunk after chunk.
     for (int i = tid; i < 2 * a.buf_floats + a.tail_floats; i += nthreads) lds[i] = 0.0f;
     __syncthreads();
-    commit(0, 0);
+    commit(cs, 0);
     __builtin_amdgcn_s_waitcnt(0);  // this wave's record copies have landed
     __syncthreads();
 
@@ -208,10 +212,10 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
 #pragma unroll
         for (int q = 0; q < Q; ++q) acc[k][q] = (f4)(0.0f);
 
-    for (int ch = 0; ch < a.n_chunks; ++ch) {
-        const int buf = ch & 1;
-        const bool more = ch + 1 < a.n_chunks;
-        if (more) fetch(ch + 1, buf ^ 1);
+    for (int ch = cs, it = 0; ch < a.n_chunks; ch += a.CS, ++it) {
+        const int buf = it & 1;
+        const bool more = ch + a.CS < a.n_chunks;
+        if (more) fetch(ch + a.CS, buf ^ 1);
 
         // ---- compute: Algorithm 2 over this chunk's nonzeros of the wave's K rows
         const int bufb = buf * win_bytes;
@@ -264,7 +268,7 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
         }
         // The other buffers were last read in the previous iteration, which every wave left
         // through the barrier below: they can be rewritten now.
-        if (more) commit(ch + 1, buf ^ 1);
+        if (more) commit(ch + a.CS, buf ^ 1);
         __builtin_amdgcn_s_waitcnt(0);  // this wave's record copies have landed
         __syncthreads();
     }
@@ -280,22 +284,41 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
             if (pos0[q] >= 0 && n0 + nloc[q] < a.N) d = dlut[pos0[q] + i];
             dofs[q][i] = d;
         }
+    // With split channels every workgroup adds its partial sums to an output that was cleared
+    // before the launch; the first split brings the bias and the clamp is a pass of its own.
+    const bool split = a.CS > 1;
     ci32p pm = as_const(a.perm) + (size_t)bin * K;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const int m = pm[k];
         if (m < 0) continue;  // uniform: padding row of the last group
-        const float bv = (a.flags & ESCOIN_F_BIAS) ? a.bias[m] : 0.0f;
+        const float bv = ((a.flags & ESCOIN_F_BIAS) && cs == 0) ? a.bias[m] : 0.0f;
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             float* __restrict__ o = a.out + ((size_t)(n0 + nloc[q]) * a.M + m) * a.EF;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 float v = acc[k][q][i] + bv;
-                if (a.flags & ESCOIN_F_RELU) v = v > 0.0f ? v : 0.0f;
-                if (dofs[q][i] >= 0) o[dofs[q][i]] = v;
+                if (dofs[q][i] < 0) continue;
+                if (split) {
+                    unsafeAtomicAdd(o + dofs[q][i], v);
+                } else {
+                    if (a.flags & ESCOIN_F_RELU) v = v > 0.0f ? v : 0.0f;
+                    o[dofs[q][i]] = v;
+                }
             }
         }
+    }
+}
+
+// out[i] = 0 / out[i] = max(out[i], 0): the passes before and after a launch with split channels.
+__global__ __launch_bounds__(256) void fill_zero_kernel(float* __restrict__ p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0.0f;
+}
+__global__ __launch_bounds__(256) void relu_kernel(float* __restrict__ p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const float v = p[i];
+        p[i] = v > 0.0f ? v : 0.0f;
     }
 }
 
@@ -354,7 +377,7 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     // the kernel's index arithmetic relies on these plan invariants
     if (h.P4 % 4 || h.plane_stride % 4 || h.P4 > h.plane_stride || h.NB < 1 || h.CC < 1 ||
         h.WQ < 1 || h.WM < 1 || h.tail_floats % 4 || h.rec_buf_bytes % 16 || h.front < 4 ||
-        h.n_phases < 1 || h.n_phases > kMaxPhases ||
+        h.n_phases < 1 || h.n_phases > kMaxPhases || h.CS < 1 || h.CS > h.n_chunks ||
         h.buf_floats != h.n_phases * h.CC * h.NB * h.plane_stride ||
         (long long)h.n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads ||
         (long long)h.buf_floats * 4 >= (1 << 24) ||
@@ -372,10 +395,10 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     a.seg = (const uint32_t*)(base + h.off_seg);
     a.rec = (const uint32_t*)(base + h.off_rec);
     a.N = d.N; a.C = d.C; a.HW = d.H * d.W; a.M = d.M; a.EF = d.E * d.F;
-    a.WM = h.WM; a.WQ = h.WQ; a.CC = h.CC; a.NB = h.NB;
+    a.WM = h.WM; a.WQ = h.WQ; a.CC = h.CC; a.NB = h.NB; a.CS = h.CS;
     a.n_tiles = h.n_tiles; a.n_mgroups = h.n_mgroups; a.n_chunks = h.n_chunks;
     const long long n_in_tiles = (long long)h.n_tiles * ((d.N + h.NB - 1) / h.NB);
-    const long long blocks = (n_in_tiles * h.n_mgroups + 7) / 8 * 8;
+    const long long blocks = (n_in_tiles * h.n_mgroups * h.CS + 7) / 8 * 8;
     if (blocks > 0x7FFFFFFFll) return ESCOIN_ERANGE;
     a.n_in_tiles = (int)n_in_tiles;
     a.plane_stride = h.plane_stride; a.P4 = h.P4; a.n_items = h.n_items;
@@ -388,5 +411,13 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return ESCOIN_EHIP;
     }
-    return launch(kern, dim3((unsigned)blocks), dim3(threads), lds_bytes, (hipStream_t)hip_stream, a);
+    if (h.CS == 1)
+        return launch(kern, dim3((unsigned)blocks), dim3(threads), lds_bytes, (hipStream_t)hip_stream, a);
+    const size_t n_out = (size_t)d.N * d.M * d.E * d.F;
+    const unsigned sweep_blocks = (unsigned)std::min<size_t>((n_out + 255) / 256, 256 * 8);
+    rc = launch(fill_zero_kernel, dim3(sweep_blocks), dim3(256), 0, (hipStream_t)hip_stream, d_out, n_out);
+    if (rc != ESCOIN_OK) return rc;
+    rc = launch(kern, dim3((unsigned)blocks), dim3(threads), lds_bytes, (hipStream_t)hip_stream, a);
+    if (rc != ESCOIN_OK || !(flags & ESCOIN_F_RELU)) return rc;
+    return launch(relu_kernel, dim3(sweep_blocks), dim3(256), 0, (hipStream_t)hip_stream, d_out, n_out);
 }

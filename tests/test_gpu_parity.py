@@ -85,6 +85,8 @@ TUNINGS = [
     dict(K=2, Q=2, B=4, WM=2, CC=6, TH=6),
     dict(K=2, Q=2, B=4, WM=16, CC=2, TH=2),
     dict(K=4, Q=1, B=4, WM=5, CC=4, TH=4),
+    dict(K=1, Q=1, B=2, WM=4, CC=2, CS=3),          # channels split over 3 workgroups, atomics
+    dict(K=2, Q=2, B=2, WM=2, CC=1, CS=2, TH=7),
 ]
 
 
@@ -100,14 +102,17 @@ def test_tiled_every_template_and_tiling(oracle, cfg, tune):
     t = dict(tune)
     if "NB" in t and "TH" not in t:
         pass
+    flags = esc.F_BIAS | (esc.F_RELU if "CS" in t else 0)   # the split path clamps in a pass of its own
     try:
         dl = DeviceLayer(esc, L, tuning=t)
-        got = dl.forward_tiled(esc.F_BIAS)
+        got = dl.forward_tiled(flags)
     except esc.EscoinError as e:
         assert e.code == esc.ERANGE       # a tiling that needs more than 8 waves or too much LDS
         pytest.skip("tiling not realisable for this shape")
-    ref, bound = oracle_full(oracle, L, esc.F_BIAS)
+    ref, bound = oracle_full(oracle, L, flags)
     assert_within_bound(got, ref, bound, f"{cfg} {tune}")
+    if "CS" in t:  # a second call must clear the first call's sums before adding to them
+        assert_within_bound(dl.forward_tiled(flags), ref, bound, f"{cfg} {tune} again")
 
 
 @pytest.mark.parametrize("path", PATHS)

@@ -22,6 +22,7 @@ CASES = [
     ((2, 3, 30, 37, 4, 3, 3, 1, 0, 0.5), dict(TH=6, Q=2)),
     ((7, 5, 7, 7, 6, 3, 3, 1, 1, 0.6), dict(K=2, NB=3)),          # idle lanes between images
     ((6, 4, 13, 13, 5, 3, 3, 1, 1, 0.6), dict(K=2, Q=2, NB=2)),   # two runs, two images
+    ((1, 12, 13, 13, 9, 3, 3, 1, 1, 0.6), dict(K=1, CC=2, CS=3)),   # channel chunks dealt to 3 workgroups
 ]
 
 
