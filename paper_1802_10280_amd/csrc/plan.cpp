@@ -356,6 +356,64 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
             used[best]++;
         }
     }
+    // Per row, chunk and class: how many nonzeros, hence how many record batches.
+    const int B = h.B;
+    std::vector<int> rcc((size_t)d.M * h.n_chunks * kClasses, 0);
+    for (int m = 0; m < d.M; ++m)
+        for (int j = rowptr[m]; j < rowptr[m + 1]; ++j)
+            rcc[((size_t)m * h.n_chunks + nz_chunk[j]) * kClasses + nz_class[j]]++;
+    // The waves of a workgroup meet at a barrier after every chunk, so a workgroup's time is
+    // the sum over chunks of its slowest wave.  Inside each workgroup the rows are dealt to the
+    // waves once more, longest first, each to the wave (with a free accumulator row) where it
+    // raises that sum the least.
+    if (h.WM > 1 && h.n_chunks > 1) {
+        std::vector<int> rows, batches((size_t)h.K * h.WM * h.n_chunks);
+        std::vector<int> wave_load((size_t)h.WM * h.n_chunks), peak(h.n_chunks), wave_rows(h.WM);
+        for (int mg = 0; mg < h.n_mgroups; ++mg) {
+            int32_t* pm = &perm[(size_t)mg * h.WM * h.K];
+            rows.clear();
+            for (int i = 0; i < h.WM * h.K; ++i)
+                if (pm[i] >= 0) rows.push_back(pm[i]);
+            std::vector<int> total(rows.size(), 0);
+            for (size_t i = 0; i < rows.size(); ++i)
+                for (int ch = 0; ch < h.n_chunks; ++ch) {
+                    int nb = 0;
+                    for (int cls = 0; cls < kClasses; ++cls)
+                        nb += ceil_div(rcc[((size_t)rows[i] * h.n_chunks + ch) * kClasses + cls], B);
+                    batches[i * h.n_chunks + ch] = nb;
+                    total[i] += nb;
+                }
+            std::vector<int> idx(rows.size());
+            std::iota(idx.begin(), idx.end(), 0);
+            std::stable_sort(idx.begin(), idx.end(), [&](int a, int b) { return total[a] > total[b]; });
+            std::fill(wave_load.begin(), wave_load.end(), 0);
+            std::fill(peak.begin(), peak.end(), 0);
+            std::fill(wave_rows.begin(), wave_rows.end(), 0);
+            std::fill(pm, pm + (size_t)h.WM * h.K, -1);
+            for (int i : idx) {
+                int best = -1;
+                long long best_rise = 0, best_total = 0;
+                for (int w = 0; w < h.WM; ++w) {
+                    if (wave_rows[w] >= h.K) continue;
+                    long long rise = 0, tot = 0;
+                    for (int ch = 0; ch < h.n_chunks; ++ch) {
+                        const int v = wave_load[(size_t)w * h.n_chunks + ch] + batches[(size_t)i * h.n_chunks + ch];
+                        rise += std::max(0, v - peak[ch]);
+                        tot += wave_load[(size_t)w * h.n_chunks + ch];
+                    }
+                    if (best < 0 || rise < best_rise || (rise == best_rise && tot < best_total)) {
+                        best = w; best_rise = rise; best_total = tot;
+                    }
+                }
+                for (int ch = 0; ch < h.n_chunks; ++ch) {
+                    int& v = wave_load[(size_t)best * h.n_chunks + ch];
+                    v += batches[(size_t)i * h.n_chunks + ch];
+                    peak[ch] = std::max(peak[ch], v);
+                }
+                pm[(size_t)best * h.K + wave_rows[best]++] = rows[i];
+            }
+        }
+    }
 
     // ---- staging items per tile: every input word the window needs and where it lives in LDS
     std::vector<std::vector<StageItem>> items(h.n_tiles);
@@ -421,14 +479,9 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
         }
 
     // ---- count batches per (group, chunk, wave, row, class); a group's chunk block is contiguous
-    const int B = h.B;
     const size_t seg_stride = 1 + (size_t)h.K * kClasses;
     std::vector<uint32_t> seg((size_t)bins * h.n_chunks * seg_stride, 0);
     std::vector<uint32_t> blk((size_t)h.n_mgroups * h.n_chunks * 2, 0);
-    std::vector<int> rcc((size_t)d.M * h.n_chunks * kClasses, 0);  // per row, chunk, class
-    for (int m = 0; m < d.M; ++m)
-        for (int j = rowptr[m]; j < rowptr[m + 1]; ++j)
-            rcc[((size_t)m * h.n_chunks + nz_chunk[j]) * kClasses + nz_class[j]]++;
     uint64_t total_batches = 0, max_block = 0;
     for (int mg = 0; mg < h.n_mgroups; ++mg) {
         for (int ch = 0; ch < h.n_chunks; ++ch) {
