@@ -3,9 +3,9 @@
 // Input: the stretched CSR of escoin_sconv_pack (offsets into the padded CHW input, Section
 // 3.1).  Output: an opaque blob holding
 //   - geometry tables, so the kernel needs no index arithmetic of its own:
-//       items:   for every input word a tile's window needs, its offset in the (unpadded)
-//                input plane and the LDS word that holds it; words of the zero frame have no
-//                item and stay +0.0f -- pad_in folded into the staging;
+//       items:   for every thread of a workgroup, the input words it stages per channel chunk:
+//                offset in the (unpadded) input and the LDS byte that holds it; words of the
+//                zero frame have no item and stay +0.0f -- pad_in folded into the staging;
 //       lanes:   which 16-byte group of the window each lane of a wave reads and which four
 //                output positions it owns;
 //       dst_lut: for every computed position of a tile, where it goes in the E*F output plane
@@ -416,7 +416,10 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     }
 
     // ---- staging items per tile: every input word the window needs and where it lives in LDS
-    std::vector<std::vector<StageItem>> items(h.n_tiles);
+    struct WindowWord {
+        int32_t src, dst;  // offset inside an H*W input plane; word index inside a window buffer
+    };
+    std::vector<std::vector<WindowWord>> items(h.n_tiles);
     const long long phase_stride = (long long)h.CC * h.NB * h.plane_stride;
     for (int t = 0; t < h.n_tiles; ++t) {
         const int h0 = t * h.TH;
@@ -427,7 +430,7 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
                 for (int jx = 0; jx < h.pitch; ++jx) {
                     const int x = jx * d.stride + g.phase_b[ph] - d.pad;
                     if (x < 0 || x >= d.W) continue;
-                    StageItem it;
+                    WindowWord it;
                     it.src = y * d.W + x;
                     it.dst = (int32_t)(ph * phase_stride + h.front + i * h.pitch + jx);
                     items[t].push_back(it);
@@ -520,7 +523,7 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     // ---- section layout
     uint64_t off = align_up64(sizeof(PlanHeader), 256);
     h.off_items = off;
-    off = align_up64(off + (uint64_t)h.n_tiles * h.n_items * sizeof(StageItem), 256);
+    off = align_up64(off + (uint64_t)h.n_tiles * kMaxItemsPerThread * threads * sizeof(StageSlot), 256);
     h.off_lanes = off;
     off = align_up64(off + (uint64_t)lanes.size() * sizeof(LaneSlot), 256);
     h.off_dst_lut = off;
@@ -543,17 +546,29 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     std::memcpy(base, &h, sizeof(h));
 
     // ---- items / lanes / dst_lut
-    StageItem* its = (StageItem*)(base + h.off_items);
+    // The (channel, image, word) triples of a chunk are dealt to the threads round-robin, so a
+    // wave's loads of one slot touch consecutive input words.
+    StageSlot* slots = (StageSlot*)(base + h.off_items);
     int32_t* dst = (int32_t*)(base + h.off_dst_lut);
     for (int t = 0; t < h.n_tiles; ++t) {
         const int h0 = t * h.TH;
-        for (int i = 0; i < h.n_items; ++i) {
-            StageItem it;
-            it.src = -1;
-            it.dst = 0;
-            if ((size_t)i < items[t].size()) it = items[t][i];
-            its[(size_t)t * h.n_items + i] = it;
-        }
+        const long long total = (long long)h.n_items * h.CC * h.NB;
+        for (int j = 0; j < kMaxItemsPerThread; ++j)
+            for (int tid = 0; tid < threads; ++tid) {
+                StageSlot sl;
+                sl.src = -1;
+                sl.key = 0;
+                const long long idx = tid + (long long)j * threads;
+                if (idx < total) {
+                    const int cn = (int)(idx / h.n_items), i = (int)(idx - (long long)cn * h.n_items);
+                    const int cl = cn / h.NB, nl = cn - cl * h.NB;
+                    if ((size_t)i < items[t].size()) {
+                        sl.src = (nl * d.C + cl) * (d.H * d.W) + items[t][i].src;
+                        sl.key = (uint32_t)((items[t][i].dst + cn * h.plane_stride) * 4) | ((uint32_t)cl << 24);
+                    }
+                }
+                slots[((size_t)t * kMaxItemsPerThread + j) * threads + tid] = sl;
+            }
         for (int p = 0; p < h.P4; ++p) {
             const int hh = p / h.pitch, w = p - hh * h.pitch;
             dst[(size_t)t * h.P4 + p] =

@@ -11,16 +11,18 @@
 namespace escoin {
 
 constexpr uint32_t kPlanMagic = 0x4E4C5045u;  // "EPLN"
-constexpr uint32_t kPlanVersion = 8;
+constexpr uint32_t kPlanVersion = 9;
 constexpr int kMaxPhases = 16;          // stride*stride phase planes
 constexpr int kClasses = 4;             // alignment classes of a tap: (LDS offset) mod 4
 constexpr int kMaxItemsPerThread = 12;  // staged input words per thread and chunk
 
-// One input word of a tile's window: where it comes from and the LDS word that holds it (for
-// channel 0 / image 0 of a window buffer).
-struct StageItem {
-    int32_t src;  // offset inside an H*W input plane, -1 = padding entry of the table
-    int32_t dst;  // word index inside a window buffer
+// One input word a thread stages per channel chunk: where it comes from and where it goes.
+struct StageSlot {
+    int32_t src;   // offset from the first input word of the chunk's first channel of the
+                   // workgroup's first image: (image*C + channel)*H*W + offset in the plane;
+                   // -1 = this thread has nothing to do in this slot
+    uint32_t key;  // bits 0..23: LDS byte offset of the word inside a window buffer;
+                   // bits 24..31: channel inside the chunk
 };
 
 // What one lane of a position run does: the 16-byte group it reads and the outputs it owns.
@@ -49,14 +51,14 @@ struct PlanHeader {
     int32_t rows_in;       // phase-plane rows held per tile
     int32_t plane_stride;  // floats per (phase, channel, image) plane in LDS (multiple of 4)
     int32_t P4;            // output positions per image and tile on the pitch grid (multiple of 4)
-    int32_t n_items;       // StageItems per tile (shorter tiles are padded with src = -1)
+    int32_t n_items;       // input words per (tile, channel, image): the longest tile's count
     int32_t buf_floats;    // floats of one LDS window buffer (two are allocated)
     int32_t tail_floats;   // zeroed floats after the second window buffer
     int32_t rec_buf_bytes; // bytes of one LDS record buffer (two are allocated)
     int32_t lds_bytes;     // dynamic LDS size
     int32_t nnz, n_records;
     // section offsets in bytes from the start of the blob
-    uint64_t off_items;    // StageItem [n_tiles][n_items]
+    uint64_t off_items;    // StageSlot [n_tiles][kMaxItemsPerThread][threads of a workgroup]
     uint64_t off_lanes;    // LaneSlot [WQ*Q][64]
     uint64_t off_dst_lut;  // int32 [n_tiles][P4]: offset in an E*F plane, or -1
     uint64_t off_perm;     // int32 [n_mgroups*WM][K]: output channel of each accumulator row, or -1

@@ -35,7 +35,7 @@ struct TiledArgs {
     const float* in;
     float* out;
     const float* bias;
-    const StageItem* items;
+    const StageSlot* stage;
     const LaneSlot* lanes;
     const int32_t* dst_lut;
     const int32_t* perm;
@@ -136,27 +136,19 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
     }
     const int base0 = base_bytes[0];
 
-    // ---- this thread's share of the staging work; the same for every chunk
+    // ---- this thread's share of the staging work (the same for every chunk), from the plan
     int st_src[kMaxItemsPerThread];  // offset from the chunk's first input word, -1 = none
     // bits 0..23: LDS byte offset of the word inside a window buffer; 24..31: channel in the chunk
     uint32_t st_key[kMaxItemsPerThread];
     {
-        const StageItem* __restrict__ its = a.items + (size_t)tile * a.n_items;
-        const int total = a.n_items * a.CC * a.NB;
+        const StageSlot* __restrict__ sl = a.stage + (size_t)tile * kMaxItemsPerThread * nthreads + tid;
+        // words of images past the end of the batch (ragged last image group) are not staged
+        const int src_end = min(a.NB, a.N - n0) * a.C * a.HW;
 #pragma unroll
         for (int j = 0; j < kMaxItemsPerThread; ++j) {
-            const int idx = tid + j * nthreads;
-            st_src[j] = -1;
-            st_key[j] = 0;
-            if (idx < total) {
-                const int cn = idx / a.n_items;
-                const StageItem it = its[idx - cn * a.n_items];
-                const int cl = cn / a.NB, nl = cn - cl * a.NB;
-                if (it.src >= 0 && n0 + nl < a.N) {
-                    st_src[j] = (nl * a.C + cl) * a.HW + it.src;
-                    st_key[j] = (uint32_t)((it.dst + cn * a.plane_stride) * 4) | ((uint32_t)cl << 24);
-                }
-            }
+            const StageSlot v = sl[(size_t)j * nthreads];
+            st_src[j] = v.src < src_end ? v.src : -1;
+            st_key[j] = v.key;
         }
     }
     const int win_bytes = a.buf_floats * 4;
@@ -284,6 +276,13 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
             if (pos0[q] >= 0 && n0 + nloc[q] < a.N) d = dlut[pos0[q] + i];
             dofs[q][i] = d;
         }
+    // A lane whose four positions are four consecutive, 16-byte aligned output words stores
+    // them at once.
+    bool quad[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+        quad[q] = (a.EF & 3) == 0 && ((uintptr_t)a.out & 15) == 0 && dofs[q][0] >= 0 && (dofs[q][0] & 3) == 0 && dofs[q][1] == dofs[q][0] + 1 &&
+                  dofs[q][2] == dofs[q][0] + 2 && dofs[q][3] == dofs[q][0] + 3;
     // With split channels every workgroup adds its partial sums to an output that was cleared
     // before the launch; the first split brings the bias and the clamp is a pass of its own.
     const bool split = a.CS > 1;
@@ -296,16 +295,23 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             float* __restrict__ o = a.out + ((size_t)(n0 + nloc[q]) * a.M + m) * a.EF;
+            f4 v = acc[k][q] + bv;
+            if (split) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float v = acc[k][q][i] + bv;
-                if (dofs[q][i] < 0) continue;
-                if (split) {
-                    unsafeAtomicAdd(o + dofs[q][i], v);
-                } else {
-                    if (a.flags & ESCOIN_F_RELU) v = v > 0.0f ? v : 0.0f;
-                    o[dofs[q][i]] = v;
-                }
+                for (int i = 0; i < 4; ++i)
+                    if (dofs[q][i] >= 0) unsafeAtomicAdd(o + dofs[q][i], v[i]);
+                continue;
+            }
+            if (a.flags & ESCOIN_F_RELU) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = v[i] > 0.0f ? v[i] : 0.0f;
+            }
+            if (quad[q]) {
+                *(f4*)__builtin_assume_aligned(o + dofs[q][0], 16) = v;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (dofs[q][i] >= 0) o[dofs[q][i]] = v[i];
             }
         }
     }
@@ -387,7 +393,7 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     const char* base = (const char*)d_plan;
     TiledArgs a;
     a.in = d_in; a.out = d_out; a.bias = d_bias;
-    a.items = (const StageItem*)(base + h.off_items);
+    a.stage = (const StageSlot*)(base + h.off_items);
     a.lanes = (const LaneSlot*)(base + h.off_lanes);
     a.dst_lut = (const int32_t*)(base + h.off_dst_lut);
     a.perm = (const int32_t*)(base + h.off_perm);

@@ -31,8 +31,10 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
     assert (C, H, W, M) == (h["C"], h["H"], h["W"], h["M"])
     K, Q, B, WM, WQ, CC, NB = h["K"], h["Q"], h["B"], h["WM"], h["WQ"], h["CC"], h["NB"]
     ps, P4 = h["plane_stride"], h["P4"]
-    items = plan[h["off_items"]:h["off_items"] + 8 * h["n_tiles"] * h["n_items"]].view(np.int32)
-    items = items.reshape(h["n_tiles"], h["n_items"], 2)
+    threads = 64 * WQ * WM
+    # staging slots: [tile][slot][thread] of (src offset, LDS byte | channel << 24)
+    slots = plan[h["off_items"]:h["off_items"] + 8 * h["n_tiles"] * 12 * threads].view(np.uint32)
+    slots = slots.reshape(h["n_tiles"], 12 * threads, 2)
     runs = WQ * Q
     lanes = plan[h["off_lanes"]:h["off_lanes"] + 12 * runs * 64].view(np.int32).reshape(runs, 64, 3)
     dst = plan[h["off_dst_lut"]:h["off_dst_lut"] + 4 * h["n_tiles"] * P4].view(np.int32).reshape(h["n_tiles"], P4)
@@ -65,8 +67,8 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
     assert buf_floats == h["n_phases"] * CC * NB * ps
     lds_len = buf_floats + h["tail_floats"]            # one window buffer plus the zeroed tail
     assert h["lds_bytes"] == (2 * buf_floats + h["tail_floats"]) * 4 + 2 * h["rec_buf_bytes"]
-    threads = 64 * WQ * WM
     assert threads <= 1024 and h["n_items"] * CC * NB <= 12 * threads
+    xflat = x.reshape(-1).astype(np.float64)
     for t in range(h["n_tiles"]):
         for n0 in range(0, N, NB):
             nb = min(NB, N - n0)
@@ -76,12 +78,13 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
                 ccur = min(CC, C - c0)
                 # the frame was zeroed once; the staging items rewrite the words that hold input
                 lds = np.zeros(lds_len)
-                for s_src, d0 in items[t]:
-                    if s_src < 0:
-                        continue
-                    for cl in range(ccur):
-                        for nl in range(nb):
-                            lds[d0 + (cl * NB + nl) * ps] = xf[n0 + nl, c0 + cl, s_src]
+                src = slots[t][:, 0].view(np.int32).astype(np.int64)
+                key = slots[t][:, 1]
+                # the kernel's tests: a slot in use, an image inside the batch, a channel inside C
+                live = (src >= 0) & (src < nb * C * H * W) & ((key >> 24) < ccur)
+                where = (key[live] & 0xFFFFFF).astype(np.int64)
+                assert np.all(where % 4 == 0) and len(set(where.tolist())) == len(where)
+                lds[where // 4] = xflat[(n0 * C + c0) * H * W + src[live]]
                 for b in range(bins):
                     mgi = b // WM
                     assert seg[b, ch, 0] + seg[b, ch, 1:].sum() <= blk[mgi, ch, 1]
