@@ -78,6 +78,17 @@ __device__ __forceinline__ f4 window_words(f4 x) {
     return (f4){from_prev_lane(x[3]), x[0], x[1], x[2]};
 }
 
+// Issue priority of this wave (0..3, higher is served first); `p` folds to a constant once the
+// calling loop is unrolled, and the instruction takes an immediate.
+__device__ __forceinline__ void set_prio(int p) {
+    switch (p) {
+        case 0: __builtin_amdgcn_s_setprio(0); break;
+        case 1: __builtin_amdgcn_s_setprio(1); break;
+        case 2: __builtin_amdgcn_s_setprio(2); break;
+        default: __builtin_amdgcn_s_setprio(3); break;
+    }
+}
+
 template <int B>
 struct Batch {
     u4 w[B / 2];  // B x {LDS byte offset, value bits}, two records per 16 bytes
@@ -251,13 +262,22 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
                 ra = rb;
             }
         };
+        // The SIMD's arbiter favours its oldest wave, so without a hint the youngest waves of
+        // the workgroup reach the chunk's barrier long after the oldest ones, which then idle.
+        // A wave lowers its issue priority as it advances through its segments: whoever is
+        // behind gets served first, and the waves arrive together.
 #pragma unroll
         for (int k = 0; k < K; ++k) {
+            set_prio(3 - (k * kClasses + 0) / K);
             run_class(std::integral_constant<int, 0>{}, acc[k], (int)cnts[1 + k * kClasses + 0]);
+            set_prio(3 - (k * kClasses + 1) / K);
             run_class(std::integral_constant<int, 1>{}, acc[k], (int)cnts[1 + k * kClasses + 1]);
+            set_prio(3 - (k * kClasses + 2) / K);
             run_class(std::integral_constant<int, 2>{}, acc[k], (int)cnts[1 + k * kClasses + 2]);
+            set_prio(3 - (k * kClasses + 3) / K);
             run_class(std::integral_constant<int, 3>{}, acc[k], (int)cnts[1 + k * kClasses + 3]);
         }
+        set_prio(3);
         // The other buffers were last read in the previous iteration, which every wave left
         // through the barrier below: they can be rewritten now.
         if (more) commit(ch + a.CS, buf ^ 1);
