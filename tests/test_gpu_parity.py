@@ -185,6 +185,28 @@ def test_all_rows_empty_gives_bias_or_zero(oracle, path):
     assert (got == L.bias[None, :, None, None]).all()
 
 
+def test_tiled_buffers_that_are_only_4_byte_aligned(oracle):
+    """Input and output that start one float past a 16-byte boundary: the 16-byte output stores
+    must give way to 4-byte ones (W and F are multiples of 4 here, so they would be used)."""
+    import torch
+    print("sconv tiled misaligned buffers", flush=True)
+    L = wl.custom_layer(2, 6, 16, 16, 8, 3, 3, 1, 1, 0.6, seed=77, dist="normal")
+    dl = DeviceLayer(esc, L)
+    ref, bound = oracle_full(oracle, L, esc.F_BIAS)
+    assert_within_bound(dl.forward_tiled(esc.F_BIAS), ref, bound, "aligned")
+    n_in, n_out = dl.d_in.numel(), dl.d_out.numel()
+    big_in = torch.zeros(n_in + 4, dtype=torch.float32, device="cuda")
+    big_out = torch.full((n_out + 8,), float("nan"), dtype=torch.float32, device="cuda")
+    big_in[1:1 + n_in] = dl.d_in.reshape(-1)
+    d_in, d_out = big_in[1:1 + n_in], big_out[1:1 + n_out]
+    assert d_out.data_ptr() % 16 == 4
+    esc.escoin_sconv_forward_tiled(dl.desc, dl.plan, dl.d_plan, d_in, d_out, dl.d_bias, esc.F_BIAS)
+    torch.cuda.synchronize()
+    got = d_out.cpu().numpy().reshape(ref.shape)
+    assert_within_bound(got, ref, bound, "misaligned")
+    assert torch.isnan(big_out[0]) and torch.isnan(big_out[1 + n_out:]).all()   # nothing written outside
+
+
 # ------------------------------------------------------------------ the paper-shaped layers
 FULL_WHOLE = ["A1b1", "A2b1", "A3b1"]                      # oracle computes every element quickly
 FULL_SAMPLED = ["R56", "R28", "R14", "R7", "R56s2", "G1", "G3", "G5", "A2b64", "S80", "S95",
