@@ -78,34 +78,34 @@ int choose_front(const Dims& d, int pitch) {
     return best_front;
 }
 
-// Pitch of a phase plane.  Rows follow each other without gaps unless rounding the pitch up to
-// a multiple of 4 costs at most 7 % more positions: then every tap row has the same alignment
-// classes (three instead of four for a 3-wide filter, so longer record segments and fewer
-// lane shifts).
-inline int plane_pitch(const Dims& d) {
-    const int p = ceil_div(d.Wp, d.stride), p4 = round_up(p, 4);
-    return p4 * 100 <= p * 107 ? p4 : p;
+// Row pitch of one image inside a phase plane.
+//   - stride 1: W + pad suffices instead of W + 2*pad.  The `pad` zero columns that follow a
+//     row's W inputs serve as its right padding and, because rows follow each other without
+//     gaps, as the left padding of what comes next; a tap never reaches further than that
+//     (its column is at most Wp - 1, i.e. `pad - 1` past those zeros' first word).
+//   - other strides: the width of a phase plane, ceil(Wp / stride).
+//   - rounded up to a multiple of 4 when that costs at most 15 % more positions (then every
+//     filter row has the same alignment classes: three instead of four for a 3-wide filter, so
+//     longer record segments and fewer lane shifts), and always when several images share a
+//     tile, so that a lane's four positions never straddle two images.
+inline int image_pitch(const Dims& d, int NB) {
+    const int p = d.stride == 1 ? d.W + d.pad : ceil_div(d.Wp, d.stride), p4 = round_up(p, 4);
+    return (NB > 1 || p4 * 100 <= p * 115) ? p4 : p;
 }
-inline int plane_stride_of(int front, int rows_in, int pitch) { return round_up(front + rows_in * pitch + 4, 4); }
-
-// Lane layout of a tile that holds NB images.  Each image takes groups_per_image + 2 entries
-// in a row (its groups and one lending group on either side).  A 16-byte LDS read is
-// conflict-free when the lanes' group numbers (word address / 4) advance by one per lane
-// modulo the 16 groups the 64 banks hold, so image n starts at the first free entry whose index
-// is congruent to its first group number; the entries skipped in between stay idle.
-// Returns the entry index of image n's first (lending) group; n == NB gives the total count.
-int image_first_entry(int n, int groups_per_image, int plane_stride) {
-    int at = 0;  // image 0: its group -1 sits at entry 0, so entry index = group number + 1 (mod 16)
-    for (int i = 1; i <= n; ++i) {
-        const int free_at = at + groups_per_image + 2;
-        const int want = (int)(((long long)i * (plane_stride / 4)) % 16);
-        at = free_at + ((want - free_at) % 16 + 16) % 16;
-    }
-    return at;
+// A tile that holds NB images lays them side by side: one wide image whose rows are the NB
+// images' rows one after the other (row pitch NB * image pitch).  Consecutive lanes then read
+// consecutive 16-byte groups whatever image they belong to (conflict-free: the group numbers of
+// the 64 lanes advance by one per lane, which is what the 64 LDS banks want), and only the two
+// ends of a run lend data instead of two lanes per image.
+inline int wide_pitch(const Dims& d, int NB) { return NB * image_pitch(d, NB); }
+// Floats of one channel's plane set (all NB images of one phase): the rows, the unused front,
+// and zeros behind the last row for its taps' right padding; a multiple of 4 * NB so that
+// the per-image share is a whole number of 16-byte groups.
+inline int wide_plane_floats(const Dims& d, int NB, int front, int rows_in) {
+    return round_up(front + rows_in * wide_pitch(d, NB) + 4 + (d.stride == 1 ? d.pad : 0), 4 * NB);
 }
-inline int lane_entries(int NB, int groups_per_image, int plane_stride) {
-    return image_first_entry(NB - 1, groups_per_image, plane_stride) + groups_per_image + 2;
-}
+// Lane-table entries of a tile: its 16-byte groups and one lending group on either side.
+inline int lane_entries(const Dims& d, int NB, int TH) { return ceil_div(TH * wide_pitch(d, NB), 4) + 2; }
 
 int build_geometry(const Dims& d, int pitch, int front, Geometry* g) {
     g->n_phases = 0;
@@ -140,7 +140,8 @@ int build_geometry(const Dims& d, int pitch, int front, Geometry* g) {
 
 // Fills every derived field of `h` from the knobs K, Q, B, WM, CC, NB, TH (already set).
 int derive(const Dims& d, PlanHeader* h, Geometry* g) {
-    h->pitch = plane_pitch(d);
+    h->pitch = wide_pitch(d, h->NB);
+    h->pitch1 = image_pitch(d, h->NB);
     h->front = choose_front(d, h->pitch);
     int rc = build_geometry(d, h->pitch, h->front, g);
     if (rc != ESCOIN_OK) return rc;
@@ -148,11 +149,11 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
     h->TH = std::min(h->TH, d.E);
     h->n_tiles = ceil_div(d.E, h->TH);
     h->rows_in = h->TH + (d.R - 1) / d.stride;
-    h->plane_stride = plane_stride_of(h->front, h->rows_in, h->pitch);
+    h->plane_stride = wide_plane_floats(d, h->NB, h->front, h->rows_in) / h->NB;
     h->P4 = round_up(h->TH * h->pitch, 4);
-    // lanes: per image the groups -1 .. P4/4 (one lending group on either side); a run of 64
-    // lanes owns the outputs of its 62 inner lanes, so consecutive runs overlap by two entries
-    const int entries = lane_entries(h->NB, h->P4 / 4, h->plane_stride);
+    // lanes: the groups -1 .. P4/4 of the (wide) tile; a run of 64 lanes owns the outputs of
+    // its 62 inner lanes, so consecutive runs overlap by two entries
+    const int entries = lane_entries(d, h->NB, h->TH);
     const int runs = std::max(1, ceil_div(entries - 2, kRunLanes));
     h->WQ = ceil_div(runs, h->Q);
     h->CC = std::min(h->CC, d.C);
@@ -181,7 +182,7 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
 void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h) {
     // the last two are searched only when the caller asks for that K or Q
     static const int kPairs[7][2] = {{4, 2}, {2, 2}, {4, 1}, {2, 1}, {1, 1}, {1, 2}, {8, 1}};
-    const int pitch = plane_pitch(d);
+    const int pitch = image_pitch(d, 1);
     const int img_groups = ceil_div(d.E * pitch, 4);
     int bestK = 2, bestQ = 1, bestTH = d.E, bestNB = 1, bestWM = 1;
     double best_score = -1.0;
@@ -208,7 +209,6 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
         }
         const int wave_groups = kRunLanes * Q;  // groups one wave can own
         const int mgroups = ceil_div(d.M, K * WM);
-        auto rows_lds = [&](int TH) { return TH + (d.R - 1) / d.stride; };
         auto consider = [&](int TH, int NB) {
             const long long wgs = (long long)ceil_div(d.E, TH) * ceil_div(d.N, NB) * mgroups;
             // the launch deals the workgroups out evenly over the 8 XCDs of 32 compute units
@@ -216,10 +216,7 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
                 (double)ceil_div(ceil_div((int)std::min<long long>(wgs, 1 << 20), 8), 32);
             // channels per chunk the staging registers allow
             const int rows = std::min(d.H, (TH - 1) * d.stride + d.R);
-            const int runs = std::max(
-                1, ceil_div(lane_entries(NB, ceil_div(TH * pitch, 4),
-                                         plane_stride_of(choose_front(d, pitch), rows_lds(TH), pitch)) - 2,
-                            kRunLanes));
+            const int runs = std::max(1, ceil_div(lane_entries(d, NB, TH) - 2, kRunLanes));
             const int WQ = ceil_div(runs, Q);
             if (WQ * WM > 16) return;
             const double cc_est = (double)kMaxItemsPerThread * 64 * WM * WQ / ((double)rows * d.W * NB);
@@ -234,11 +231,10 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
             }
         };
         if (img_groups <= wave_groups) {  // whole images: NB of them per workgroup
-            const int ps = plane_stride_of(choose_front(d, pitch), d.E + (d.R - 1) / d.stride, pitch);
             int nb_max = 1;
-            while (nb_max < d.N && lane_entries(nb_max + 1, img_groups, ps) - 2 <= wave_groups) ++nb_max;
+            while (nb_max < d.N && lane_entries(d, nb_max + 1, d.E) - 2 <= wave_groups) ++nb_max;
             for (int NB = nb_max; NB >= 1; --NB) {
-                if (ceil_div(lane_entries(NB, img_groups, ps) - 2, kRunLanes) < Q) break;  // idle position run
+                if (ceil_div(lane_entries(d, NB, d.E) - 2, kRunLanes) < Q) break;  // idle position run
                 consider(d.E, NB);
             }
         } else {  // a band of rows of one image
@@ -264,7 +260,7 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
         Geometry g;
         PlanHeader probe = *h;
         probe.CC = 1;
-        const int lds_target = 100 * 1024;
+        const int lds_target = 128 * 1024;  // the rest holds the two record buffers
         if (derive(d, &probe, &g) == ESCOIN_OK) {
             const int per_c = 2 * probe.n_phases * probe.NB * probe.plane_stride * 4;
             h->CC = std::max(1, std::min(d.C, lds_target / per_c));
@@ -427,7 +423,7 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
             for (int i = 0; i < h.rows_in; ++i) {
                 const int y = (h0 + i) * d.stride + g.phase_a[ph] - d.pad;
                 if (y < 0 || y >= d.H) continue;
-                for (int jx = 0; jx < h.pitch; ++jx) {
+                for (int jx = 0; jx < h.pitch1; ++jx) {  // image 0; image nl sits nl * pitch1 further
                     const int x = jx * d.stride + g.phase_b[ph] - d.pad;
                     if (x < 0 || x >= d.W) continue;
                     WindowWord it;
@@ -447,21 +443,12 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     // ---- lanes of every position run
     const int gpi = h.P4 / 4;
     std::vector<LaneSlot> entries;
-    for (int nl = 0; nl < h.NB; ++nl) {
-        const size_t first = (size_t)image_first_entry(nl, gpi, h.plane_stride);
-        while (entries.size() < first) {  // idle entries keep walking through the banks
-            LaneSlot e = entries.back();
-            e.base_word += 4;
-            e.pos0 = -1;
-            entries.push_back(e);
-        }
-        for (int gi = -1; gi <= gpi; ++gi) {
-            LaneSlot e;
-            e.base_word = nl * h.plane_stride + 4 * gi;
-            e.pos0 = (gi >= 0 && gi < gpi) ? 4 * gi : -1;
-            e.nloc = nl;
-            entries.push_back(e);
-        }
+    for (int gi = -1; gi <= gpi; ++gi) {
+        LaneSlot e;
+        e.base_word = 4 * gi;
+        e.pos0 = (gi >= 0 && gi < gpi) ? 4 * gi : -1;
+        e.nloc = gi >= 0 ? ((4 * gi) % h.pitch) / h.pitch1 : 0;  // which of the images side by side
+        entries.push_back(e);
     }
     const int runs = h.WQ * h.Q;
     std::vector<LaneSlot> lanes((size_t)runs * 64);
@@ -564,13 +551,16 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
                     const int cl = cn / h.NB, nl = cn - cl * h.NB;
                     if ((size_t)i < items[t].size()) {
                         sl.src = (nl * d.C + cl) * (d.H * d.W) + items[t][i].src;
-                        sl.key = (uint32_t)((items[t][i].dst + cn * h.plane_stride) * 4) | ((uint32_t)cl << 24);
+                        // channel cl's plane set, then image nl's columns inside the wide rows
+                        const long long word =
+                            items[t][i].dst + (long long)cl * h.NB * h.plane_stride + nl * h.pitch1;
+                        sl.key = (uint32_t)(word * 4) | ((uint32_t)cl << 24);
                     }
                 }
                 slots[((size_t)t * kMaxItemsPerThread + j) * threads + tid] = sl;
             }
         for (int p = 0; p < h.P4; ++p) {
-            const int hh = p / h.pitch, w = p - hh * h.pitch;
+            const int hh = p / h.pitch, w = (p - hh * h.pitch) % h.pitch1;  // column inside its image
             dst[(size_t)t * h.P4 + p] =
                 (hh < h.TH && h0 + hh < d.E && w < d.F) ? (h0 + hh) * d.F + w : -1;
         }
@@ -654,7 +644,8 @@ int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_
         rc = build_plan_once(d, rowptr, stretched, value, h, out, out_bytes, bytes);
         if (rc != ESCOIN_ERANGE) return rc;
         if (auto_cc && h.CC > 1) {
-            h.CC = std::max(1, h.CC * 3 / 4);
+            h.CC = std::max(1, h.CC - std::max(1, h.CC / 8));
+            h.CC = ceil_div(d.C, ceil_div(d.C, h.CC));  // equal chunks again
         } else if (auto_tile && h.NB > 1) {
             h.NB = h.NB / 2;
         } else if (auto_tile && h.TH > 1) {

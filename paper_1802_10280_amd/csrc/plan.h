@@ -11,7 +11,7 @@
 namespace escoin {
 
 constexpr uint32_t kPlanMagic = 0x4E4C5045u;  // "EPLN"
-constexpr uint32_t kPlanVersion = 9;
+constexpr uint32_t kPlanVersion = 10;
 constexpr int kMaxPhases = 16;          // stride*stride phase planes
 constexpr int kClasses = 4;             // alignment classes of a tap: (LDS offset) mod 4
 constexpr int kMaxItemsPerThread = 12;  // staged input words per thread and chunk
@@ -46,11 +46,11 @@ struct PlanHeader {
     int32_t NB;  // images per workgroup
     int32_t TH;  // output rows per tile (band height)
     int32_t n_tiles, n_mgroups, n_chunks, n_phases;
-    int32_t pitch;         // row pitch of a phase plane in LDS (floats)
+    int32_t pitch;         // row pitch of a phase plane in LDS (floats): NB images side by side
     int32_t front;         // unused floats in front of every LDS plane
     int32_t rows_in;       // phase-plane rows held per tile
-    int32_t plane_stride;  // floats per (phase, channel, image) plane in LDS (multiple of 4)
-    int32_t P4;            // output positions per image and tile on the pitch grid (multiple of 4)
+    int32_t plane_stride;  // floats per (phase, channel) plane set in LDS divided by NB (multiple of 4)
+    int32_t P4;            // positions of a tile (all its images) on the pitch grid (multiple of 4)
     int32_t n_items;       // input words per (tile, channel, image): the longest tile's count
     int32_t buf_floats;    // floats of one LDS window buffer (two are allocated)
     int32_t tail_floats;   // zeroed floats after the second window buffer
@@ -67,8 +67,9 @@ struct PlanHeader {
                            // block, then batches per (row, class)
     uint64_t off_rec;      // {uint32 lds_byte_offset, float value} records, B per batch
     uint64_t total_bytes;
-    int32_t CS;  // workgroups that share an output tile; each takes every CS-th channel chunk
-    uint32_t reserved[7];
+    int32_t CS;      // workgroups that share an output tile; each takes every CS-th channel chunk
+    int32_t pitch1;  // columns of one image inside a row of `pitch` floats (pitch = NB * pitch1)
+    uint32_t reserved[6];
 };
 
 }  // namespace escoin

@@ -401,7 +401,7 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     const int threads = 64 * h.WQ * h.WM;
     if (threads > 1024 || threads <= 0) return ESCOIN_EINVAL;
     // the kernel's index arithmetic relies on these plan invariants
-    if (h.P4 % 4 || h.plane_stride % 4 || h.P4 > h.plane_stride || h.NB < 1 || h.CC < 1 ||
+    if (h.P4 % 4 || h.plane_stride % 4 || (long long)h.P4 > (long long)h.NB * h.plane_stride || h.NB < 1 || h.CC < 1 ||
         h.WQ < 1 || h.WM < 1 || h.tail_floats % 4 || h.rec_buf_bytes % 16 || h.front < 4 ||
         h.n_phases < 1 || h.n_phases > kMaxPhases || h.CS < 1 || h.CS > h.n_chunks ||
         h.buf_floats != h.n_phases * h.CC * h.NB * h.plane_stride ||

@@ -49,15 +49,17 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
     rec_off = rec.view(np.uint32)[0::2]
     rec_val = rec.view(np.float32)[1::2]
     assert sorted(perm[perm >= 0].tolist()) == list(range(M)), "perm must cover every row once"
-    # every position of every image is owned by exactly one lane
-    owned = np.zeros((NB, P4), dtype=int)
+    # every position of the (wide) tile is owned by exactly one lane
+    assert h["pitch"] == NB * h["pitch1"] and h["pitch1"] >= 1
+    owned = np.zeros(P4, dtype=int)
     for r in range(runs):
         for l in range(64):
             b, p0, nl = lanes[r, l]
             if p0 >= 0:
-                assert 0 < l < 63 and b == nl * ps + p0
-                owned[nl, p0:p0 + 4] += 1
-                # both neighbours hold the adjacent groups of the same plane
+                assert 0 < l < 63 and b == p0 and nl == (p0 % h["pitch"]) // h["pitch1"]
+                assert ((p0 + 3) % h["pitch"]) // h["pitch1"] == nl, "a lane's positions straddle two images"
+                owned[p0:p0 + 4] += 1
+                # both neighbours hold the adjacent groups
                 assert lanes[r, l - 1, 0] == b - 4 and lanes[r, l + 1, 0] == b + 4
     assert (owned == 1).all(), "lane table must own every position once"
 

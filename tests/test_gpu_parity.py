@@ -57,6 +57,11 @@ SMALL = [
     (1, 2, 9, 9, 3, 2, 3, 3, 2, 0.3),        # R != S, stride 3
     (2, 12, 13, 13, 9, 3, 3, 1, 1, 0.0),     # dense rows (0 % sparsity)
     (5, 20, 7, 7, 12, 3, 3, 1, 1, 0.8),      # 7x7 maps
+    (3, 4, 9, 10, 5, 3, 3, 1, 2, 0.5),       # more padding than the filter needs
+    (2, 5, 8, 8, 4, 1, 1, 1, 1, 0.4),        # 1x1 with a frame of zeros (bias-only border)
+    (2, 3, 12, 11, 4, 7, 7, 1, 3, 0.6),      # 7x7 stride 1: three shared padding columns
+    (3, 4, 9, 9, 5, 4, 4, 1, 1, 0.5),        # even filter: reaches further right than left
+    (9, 6, 5, 6, 7, 3, 3, 1, 1, 0.5),        # many small images side by side in one tile
 ]
 
 

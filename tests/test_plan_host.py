@@ -23,6 +23,12 @@ CASES = [
     ((7, 5, 7, 7, 6, 3, 3, 1, 1, 0.6), dict(K=2, NB=3)),          # idle lanes between images
     ((6, 4, 13, 13, 5, 3, 3, 1, 1, 0.6), dict(K=2, Q=2, NB=2)),   # two runs, two images
     ((1, 12, 13, 13, 9, 3, 3, 1, 1, 0.6), dict(K=1, CC=2, CS=3)),   # channel chunks dealt to 3 workgroups
+    ((3, 4, 9, 10, 5, 3, 3, 1, 2, 0.5), {}),                         # more padding than the filter needs
+    ((2, 5, 8, 8, 4, 1, 1, 1, 1, 0.4), dict(NB=2)),                  # 1x1 with a frame of zeros
+    ((2, 3, 12, 11, 4, 7, 7, 1, 3, 0.6), {}),                        # 7x7 stride 1
+    ((3, 4, 9, 9, 5, 4, 4, 1, 1, 0.5), dict(NB=3)),                  # even filter
+    ((9, 6, 5, 6, 7, 3, 3, 1, 1, 0.5), dict(NB=4)),                  # four images side by side, ragged last group
+    ((5, 3, 6, 5, 4, 3, 3, 2, 1, 0.5), dict(NB=2)),                  # stride 2 with two images per tile
 ]
 
 
@@ -94,9 +100,9 @@ def test_lanes_walk_through_the_lds_banks(name, tune):
     group = lanes[:, :, 0] // 4
     for r in range(runs):
         assert len(set((group[r] - np.arange(64)) % 16)) == 1, (name, r)
-    assert lanes[:, :, 0].min() == -4 and lanes[:, :, 0].max() <= h["NB"] * h["plane_stride"]
+    assert lanes[:, :, 0].min() == -4 and lanes[:, :, 0].max() <= h["P4"]
     owned = lanes[:, :, 1] >= 0
-    assert owned.sum() == h["NB"] * h["P4"] // 4                  # every group owned exactly once
+    assert owned.sum() == h["P4"] // 4                            # every group owned exactly once
 
 
 def test_plan_error_paths():
