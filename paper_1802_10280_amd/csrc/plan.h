@@ -28,8 +28,8 @@ struct StageSlot {
 // What one lane of a position run does: the 16-byte group it reads and the outputs it owns.
 struct LaneSlot {
     int32_t base_word;  // word index of the group inside a (channel 0) plane set
-    int32_t pos0;       // first of its 4 positions inside the image's tile, -1 = nothing to store
-    int32_t nloc;       // image inside the workgroup's image group
+    int32_t pos0;       // first of its 4 positions inside the tile (index into dst_lut), -1 = nothing to store
+    int32_t nloc;       // which of the tile's NB images those positions belong to
 };
 
 struct PlanHeader {
