@@ -212,6 +212,36 @@ def test_tiled_buffers_that_are_only_4_byte_aligned(oracle):
     assert torch.isnan(big_out[0]) and torch.isnan(big_out[1 + n_out:]).all()   # nothing written outside
 
 
+# Shapes outside the bundled workloads, in the plan's default tiling: first layers of the
+# paper's networks, 1x1 layers with many channels, large and very wide images.
+ODD_SHAPES = [
+    # N, C, H, W, M, R, S, stride, pad, sparsity
+    (2, 3, 224, 224, 64, 7, 7, 2, 3, 0.5),
+    (1, 3, 227, 227, 96, 11, 11, 4, 0, 0.5),
+    (2, 64, 56, 56, 256, 1, 1, 1, 0, 0.7),
+    (5, 512, 7, 7, 1024, 1, 1, 1, 0, 0.8),
+    (2, 32, 112, 112, 32, 3, 3, 1, 1, 0.8),
+    (3, 16, 5, 300, 8, 3, 3, 1, 1, 0.6),
+    (2, 8, 70, 9, 6, 5, 3, 1, 2, 0.6),
+    (70, 4, 3, 3, 5, 3, 3, 1, 1, 0.5),
+]
+
+
+@pytest.mark.parametrize("cfg", ODD_SHAPES, ids=lambda c: "x".join(map(str, c)))
+def test_tiled_default_tiling_on_other_shapes(oracle, cfg):
+    print("sconv tiled other shapes", cfg, flush=True)
+    N, C, H, W, M, R, S, stride, pad, sp = cfg
+    L = wl.custom_layer(N, C, H, W, M, R, S, stride, pad, sp, seed=sum(cfg[:9]) + 5, dist="normal")
+    s = L.spec
+    dl = DeviceLayer(esc, L)
+    got = dl.forward_tiled(esc.F_BIAS)
+    assert np.isfinite(got).all()                       # the buffer was NaN-filled before the call
+    pts = sample_points(s, 3000, seed=11)
+    Wd = oracle.csr_to_dense(s.M, s.C, s.R, s.S, L.rowptr, L.colidx, L.value)
+    ref, bound = oracle.conv_points(L.input, Wd, pts, s.stride, s.pad, bias=L.bias, flags=esc.F_BIAS)
+    assert_within_bound(got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], ref, bound, str(cfg))
+
+
 # ------------------------------------------------------------------ the paper-shaped layers
 FULL_WHOLE = ["A1b1", "A2b1", "A3b1"]                      # oracle computes every element quickly
 FULL_SAMPLED = ["R56", "R28", "R14", "R7", "R56s2", "G1", "G3", "G5", "A2b64", "S80", "S95",
