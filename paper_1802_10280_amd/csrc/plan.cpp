@@ -37,7 +37,8 @@
 
 namespace escoin {
 
-bool tiled_variant_exists(int K, int Q, int B);  // sconv_tiled.hip
+bool tiled_variant_exists(int K, int Q, int B);       // sconv_tiled.hip
+bool tiled_wide_staging_exists(int K, int Q, int B);  // sconv_tiled.hip
 
 namespace {
 
@@ -434,8 +435,18 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
             }
         }
     }
+    // Input order (row, column): with full-width tiles every row is complete, so when W is a
+    // multiple of 4 the words of a tile come in runs of 4 consecutive, 16-byte aligned input
+    // words that one wide load can fetch (if the kernel variant has such loads).
+    h.VW = (d.W % 4 == 0 && tiled_wide_staging_exists(h.K, h.Q, h.B)) ? 4 : 1;
+    for (auto& v : items) {
+        std::stable_sort(v.begin(), v.end(), [](const WindowWord& a, const WindowWord& b) { return a.src < b.src; });
+        for (size_t i = 0; i < v.size() && h.VW > 1; ++i)
+            if (v[i].src % h.VW != (int)(i % h.VW) || (i % h.VW && v[i].src != v[i - 1].src + 1)) h.VW = 1;
+    }
     size_t n_items = 0;
     for (auto& v : items) n_items = std::max(n_items, v.size());
+    if (n_items % h.VW) h.VW = 1;
     n_items = std::max<size_t>(n_items, 1);
     if ((long long)n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads) return ESCOIN_ERANGE;
     h.n_items = (int32_t)n_items;
@@ -539,15 +550,19 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     int32_t* dst = (int32_t*)(base + h.off_dst_lut);
     for (int t = 0; t < h.n_tiles; ++t) {
         const int h0 = t * h.TH;
-        const long long total = (long long)h.n_items * h.CC * h.NB;
+        // Runs of VW words are dealt to the threads round-robin (a wave's loads of one slot
+        // touch consecutive runs); a thread's slots j*VW .. j*VW+VW-1 hold one run.
+        const int n_runs = h.n_items / h.VW;
+        const long long total_runs = (long long)n_runs * h.CC * h.NB;
         for (int j = 0; j < kMaxItemsPerThread; ++j)
             for (int tid = 0; tid < threads; ++tid) {
                 StageSlot sl;
                 sl.src = -1;
                 sl.key = 0;
-                const long long idx = tid + (long long)j * threads;
-                if (idx < total) {
-                    const int cn = (int)(idx / h.n_items), i = (int)(idx - (long long)cn * h.n_items);
+                const long long run = tid + (long long)(j / h.VW) * threads;
+                if (run < total_runs) {
+                    const int cn = (int)(run / n_runs);
+                    const int i = (int)(run - (long long)cn * n_runs) * h.VW + j % h.VW;
                     const int cl = cn / h.NB, nl = cn - cl * h.NB;
                     if ((size_t)i < items[t].size()) {
                         sl.src = (nl * d.C + cl) * (d.H * d.W) + items[t][i].src;

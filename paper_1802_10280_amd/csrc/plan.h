@@ -11,7 +11,7 @@
 namespace escoin {
 
 constexpr uint32_t kPlanMagic = 0x4E4C5045u;  // "EPLN"
-constexpr uint32_t kPlanVersion = 10;
+constexpr uint32_t kPlanVersion = 11;
 constexpr int kMaxPhases = 16;          // stride*stride phase planes
 constexpr int kClasses = 4;             // alignment classes of a tap: (LDS offset) mod 4
 constexpr int kMaxItemsPerThread = 12;  // staged input words per thread and chunk
@@ -69,7 +69,9 @@ struct PlanHeader {
     uint64_t total_bytes;
     int32_t CS;      // workgroups that share an output tile; each takes every CS-th channel chunk
     int32_t pitch1;  // columns of one image inside a row of `pitch` floats (pitch = NB * pitch1)
-    uint32_t reserved[6];
+    int32_t VW;      // a thread's staging slots come in runs of VW (4 or 1) consecutive input
+                     // words whose first is VW-word aligned inside the input tensor
+    uint32_t reserved[5];
 };
 
 }  // namespace escoin

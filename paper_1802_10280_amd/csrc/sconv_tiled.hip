@@ -110,7 +110,9 @@ constexpr int kRunStrideBytes = 62 * 16;
 
 // CONTIG: the workgroup's tile holds one image, so a lane's groups in consecutive position runs
 // are kRunStrideBytes apart and the second LDS read needs no address arithmetic of its own.
-template <int K, int Q, int B, bool CONTIG>
+// VW: input words per staging load (4: the plan dealt the window words in runs of four
+// consecutive, 16-byte aligned input words and the input pointer is 16-byte aligned; 1: any plan).
+template <int K, int Q, int B, bool CONTIG, int VW>
 __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     char* const lds_bytes = (char*)lds;
@@ -148,7 +150,8 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
     const int base0 = base_bytes[0];
 
     // ---- this thread's share of the staging work (the same for every chunk), from the plan
-    int st_src[kMaxItemsPerThread];  // offset from the chunk's first input word, -1 = none
+    constexpr int kRuns = kMaxItemsPerThread / VW;
+    int st_src[kRuns];  // per run of VW words: offset from the chunk's first input word, -1 = none
     // bits 0..23: LDS byte offset of the word inside a window buffer; 24..31: channel in the chunk
     uint32_t st_key[kMaxItemsPerThread];
     {
@@ -158,7 +161,7 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
 #pragma unroll
         for (int j = 0; j < kMaxItemsPerThread; ++j) {
             const StageSlot v = sl[(size_t)j * nthreads];
-            st_src[j] = v.src < src_end ? v.src : -1;
+            if (j % VW == 0) st_src[j / VW] = v.src < src_end ? v.src : -1;
             st_key[j] = v.key;
         }
     }
@@ -178,8 +181,15 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
         const int ccur = min(a.CC, a.C - c0);
         const float* __restrict__ src = a.in + ((size_t)n0 * a.C + c0) * a.HW;
 #pragma unroll
-        for (int j = 0; j < kMaxItemsPerThread; ++j)
-            if (st_src[j] >= 0 && (int)(st_key[j] >> 24) < ccur) st_val[j] = src[st_src[j]];
+        for (int r = 0; r < kRuns; ++r)
+            if (st_src[r] >= 0 && (int)(st_key[r * VW] >> 24) < ccur) {
+                if (VW == 4) {
+                    const f4 v = *(const f4*)__builtin_assume_aligned(src + st_src[r], 16);
+                    st_val[4 * r] = v[0]; st_val[4 * r + 1] = v[1]; st_val[4 * r + 2] = v[2]; st_val[4 * r + 3] = v[3];
+                } else {
+                    st_val[r] = src[st_src[r]];
+                }
+            }
         const char* rsrc = (const char*)(a.rec + (size_t)blkp[2 * ch] * (2 * B));
         const int units = (int)blkp[2 * ch + 1] * (B / 2);  // 16-byte units in the block
         char* const rb = lds_bytes + rec_base + buf * a.rec_buf_bytes;
@@ -195,7 +205,7 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
         char* const win = lds_bytes + buf * win_bytes;
 #pragma unroll
         for (int j = 0; j < kMaxItemsPerThread; ++j)
-            if (st_src[j] >= 0 && (int)(st_key[j] >> 24) < ccur)
+            if (st_src[j / VW] >= 0 && (int)(st_key[j] >> 24) < ccur)
                 *(float*)(win + (st_key[j] & 0xFFFFFF)) = st_val[j];
     };
 
@@ -354,21 +364,41 @@ typedef void (*TiledKernel)(const TiledArgs);
 #define ESCOIN_TILED_VARIANTS(X) \
     X(1, 1, 2) X(1, 2, 2) X(2, 1, 2) X(2, 1, 4) X(2, 2, 2) X(2, 2, 4) X(4, 1, 2) X(4, 1, 4) X(4, 2, 2) X(8, 1, 2) X(8, 1, 4)
 
-template <int K, int Q, int B>
+// The instantiations that also exist with 16-byte staging loads (fewer load instructions and
+// nine registers less; the ones the layers with W % 4 == 0 of the bundled workloads use).
+#define ESCOIN_TILED_WIDE_STAGING(X) X(1, 1, 2) X(2, 1, 2) X(4, 1, 2) X(2, 2, 2) X(4, 2, 2)
+
+template <int K, int Q, int B, int VW>
 TiledKernel instance(bool contig) {
-    if (Q > 1 && contig) return sconv_tiled_kernel<K, Q, B, true>;
-    return sconv_tiled_kernel<K, Q, B, false>;
+    if constexpr (Q > 1) {
+        if (contig) return sconv_tiled_kernel<K, Q, B, true, VW>;
+    }
+    return sconv_tiled_kernel<K, Q, B, false, VW>;
 }
 
-TiledKernel pick(int K, int Q, int B, bool contig) {
+TiledKernel pick(int K, int Q, int B, bool contig, bool wide_staging) {
+    if (wide_staging) {
 #define ESCOIN_PICK(KK, QQ, BB) \
-    if (K == KK && Q == QQ && B == BB) return instance<KK, QQ, BB>(contig);
+    if (K == KK && Q == QQ && B == BB) return instance<KK, QQ, BB, 4>(contig);
+        ESCOIN_TILED_WIDE_STAGING(ESCOIN_PICK)
+#undef ESCOIN_PICK
+    }
+#define ESCOIN_PICK(KK, QQ, BB) \
+    if (K == KK && Q == QQ && B == BB) return instance<KK, QQ, BB, 1>(contig);
     ESCOIN_TILED_VARIANTS(ESCOIN_PICK)
 #undef ESCOIN_PICK
     return nullptr;
 }
 
 }  // namespace
+
+bool tiled_wide_staging_exists(int K, int Q, int B) {
+#define ESCOIN_HAS(KK, QQ, BB) \
+    if (K == KK && Q == QQ && B == BB) return true;
+    ESCOIN_TILED_WIDE_STAGING(ESCOIN_HAS)
+#undef ESCOIN_HAS
+    return false;
+}
 
 bool tiled_variant_exists(int K, int Q, int B) {
 #define ESCOIN_HAS(KK, QQ, BB) \
@@ -396,14 +426,15 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     if (h.C != d.C || h.H != d.H || h.W != d.W || h.M != d.M || h.R != d.R || h.S != d.S ||
         h.stride != d.stride || h.pad != d.pad || h.E != d.E || h.F != d.F)
         return ESCOIN_EINVAL;
-    TiledKernel kern = pick(h.K, h.Q, h.B, h.NB == 1);
+    // 16-byte staging loads need the plan's runs of four words and a 16-byte aligned input
+    TiledKernel kern = pick(h.K, h.Q, h.B, h.NB == 1, h.VW == 4 && ((uintptr_t)d_in & 15) == 0);
     if (!kern) return ESCOIN_EINVAL;
     const int threads = 64 * h.WQ * h.WM;
     if (threads > 1024 || threads <= 0) return ESCOIN_EINVAL;
     // the kernel's index arithmetic relies on these plan invariants
     if (h.P4 % 4 || h.plane_stride % 4 || (long long)h.P4 > (long long)h.NB * h.plane_stride || h.NB < 1 || h.CC < 1 ||
         h.WQ < 1 || h.WM < 1 || h.tail_floats % 4 || h.rec_buf_bytes % 16 || h.front < 4 ||
-        h.n_phases < 1 || h.n_phases > kMaxPhases || h.CS < 1 || h.CS > h.n_chunks ||
+        h.n_phases < 1 || h.n_phases > kMaxPhases || (h.VW != 1 && h.VW != 4) || h.CS < 1 || h.CS > h.n_chunks ||
         h.buf_floats != h.n_phases * h.CC * h.NB * h.plane_stride ||
         (long long)h.n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads ||
         (long long)h.buf_floats * 4 >= (1 << 24) ||
