@@ -150,6 +150,10 @@ def main():
             "binding": "alu" if t_alu >= t_hbm else "hbm",
             "binding_frac": round(max(t_alu, t_hbm) / t_all, 4),
         })
+        # achieved GB/s: HBM-side bytes the counters recorded for this layer and tiling, if any
+        moved_hw = r.measured_traffic()
+        rows[-1]["traffic_bytes"] = moved_hw
+        rows[-1]["gbps_measured"] = round(moved_hw / t_sconv / 1e6, 1) if moved_hw else None
     dom = max(range(len(rows)), key=lambda k: rows[k]["us_sconv"])
     Ld, rd = layers[dom], rows[dom]
     if rd["binding"] == "alu":
