@@ -83,14 +83,15 @@ int choose_front(const Dims& d, int pitch) {
 //   - stride 1: W + pad suffices instead of W + 2*pad.  The `pad` zero columns that follow a
 //     row's W inputs serve as its right padding and, because rows follow each other without
 //     gaps, as the left padding of what comes next; a tap never reaches further than that
-//     (its column is at most Wp - 1, i.e. `pad - 1` past those zeros' first word).
+//     (its column is at most Wp - 1, i.e. `pad - 1` past those zeros' first word).  A row of
+//     outputs must fit as well: with more padding than the filter needs F exceeds W + pad.
 //   - other strides: the width of a phase plane, ceil(Wp / stride).
 //   - rounded up to a multiple of 4 when that costs at most 15 % more positions (then every
 //     filter row has the same alignment classes: three instead of four for a 3-wide filter, so
 //     longer record segments and fewer lane shifts), and always when several images share a
 //     tile, so that a lane's four positions never straddle two images.
 inline int image_pitch(const Dims& d, int NB) {
-    const int p = d.stride == 1 ? d.W + d.pad : ceil_div(d.Wp, d.stride), p4 = round_up(p, 4);
+    const int p = d.stride == 1 ? std::max(d.W + d.pad, d.F) : ceil_div(d.Wp, d.stride), p4 = round_up(p, 4);
     return (NB > 1 || p4 * 100 <= p * 115) ? p4 : p;
 }
 // A tile that holds NB images lays them side by side: one wide image whose rows are the NB

@@ -62,6 +62,7 @@ SMALL = [
     (2, 3, 12, 11, 4, 7, 7, 1, 3, 0.6),      # 7x7 stride 1: three shared padding columns
     (3, 4, 9, 9, 5, 4, 4, 1, 1, 0.5),        # even filter: reaches further right than left
     (9, 6, 5, 6, 7, 3, 3, 1, 1, 0.5),        # many small images side by side in one tile
+    (5, 6, 11, 1, 10, 4, 1, 1, 3, 0.0),      # one input column, output rows wider than W + pad
 ]
 
 

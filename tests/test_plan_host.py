@@ -29,6 +29,7 @@ CASES = [
     ((3, 4, 9, 9, 5, 4, 4, 1, 1, 0.5), dict(NB=3)),                  # even filter
     ((9, 6, 5, 6, 7, 3, 3, 1, 1, 0.5), dict(NB=4)),                  # four images side by side, ragged last group
     ((5, 3, 6, 5, 4, 3, 3, 2, 1, 0.5), dict(NB=2)),                  # stride 2 with two images per tile
+    ((5, 6, 11, 1, 10, 4, 1, 1, 3, 0.0), dict(CC=3, NB=3)),          # output rows wider than W + pad
 ]
 
 
@@ -47,6 +48,47 @@ def test_plan_replay_matches_oracle(oracle, cfg, tune):
     Wd = oracle.csr_to_dense(M, C, R, S, L.rowptr, L.colidx, L.value)
     ref, bound = oracle.conv(L.input, Wd, stride, pad)
     assert np.all(np.abs(got - ref) <= 1e-6 * bound + 1e-12)
+
+
+def test_random_layers_and_tilings_replay(oracle):
+    """Seeded random small layers (any filter size, stride, padding) with random knobs: every
+    plan the builder accepts must replay to the oracle's result."""
+    rng = np.random.default_rng(20260)
+    done = 0
+    for it in range(90):
+        R, S = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        stride, pad = int(rng.choice([1, 1, 1, 2, 3])), int(rng.integers(0, 4))
+        H = int(rng.integers(max(1, R - 2 * pad), 20))
+        W = int(rng.integers(max(1, S - 2 * pad), 30))
+        N, C, M = int(rng.integers(1, 9)), int(rng.integers(1, 7)), int(rng.integers(1, 10))
+        L = wl.custom_layer(N, C, H, W, M, R, S, stride, pad, float(rng.choice([0.0, 0.5, 0.9])),
+                            seed=5000 + it, dist="normal")
+        tune = {}
+        if rng.random() < 0.7:
+            tune["K"], tune["Q"] = [(1, 1), (1, 2), (2, 1), (2, 2), (4, 1), (4, 2), (8, 1)][int(rng.integers(0, 7))]
+        if rng.random() < 0.5:
+            tune["WM"] = int(rng.integers(1, 5))
+        if rng.random() < 0.5:
+            tune["CC"] = int(rng.integers(1, C + 1))
+        if rng.random() < 0.4:
+            tune["NB"] = int(rng.integers(1, N + 1))
+        elif rng.random() < 0.4:
+            tune["TH"] = int(rng.integers(1, L.spec.E + 1))
+        if rng.random() < 0.3:
+            tune["CS"] = int(rng.integers(1, 4))
+        d = esc.desc_of(L.spec)
+        st = esc.escoin_sconv_pack(d, L.rowptr, L.colidx)
+        try:
+            plan = esc.escoin_sconv_plan_build(d, L.rowptr, st, L.value, esc.make_tuning(**tune))
+        except esc.EscoinError as e:
+            assert e.code in (esc.ERANGE, esc.EINVAL), (L.spec, tune)   # a tiling that cannot be realised
+            continue
+        got = simulate(plan, L.input, M)
+        Wd = oracle.csr_to_dense(M, C, R, S, L.rowptr, L.colidx, L.value)
+        ref, bound = oracle.conv(L.input, Wd, stride, pad)
+        assert np.all(np.abs(got - ref) <= 1e-6 * bound + 1e-12), (L.spec, tune)
+        done += 1
+    assert done >= 70
 
 
 def test_plan_accepts_unsorted_rows_and_duplicates(oracle):
