@@ -243,6 +243,51 @@ def test_tiled_default_tiling_on_other_shapes(oracle, cfg):
     assert_within_bound(got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], ref, bound, str(cfg))
 
 
+def test_tiled_random_layers_and_tilings(oracle):
+    """Seeded random small layers (filter up to 7x7, strides 1-3, padding 0-3, some with rows of
+    whole 16-byte groups) with random knobs and flags; every tiling the plan builder accepts."""
+    rng = np.random.default_rng(1802)
+    done = 0
+    for it in range(200):
+        big = rng.random() < 0.3
+        R, S = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        stride, pad = int(rng.choice([1, 1, 1, 2, 3])), int(rng.integers(0, 4))
+        H = int(rng.integers(max(1, R - 2 * pad), 40 if big else 20))
+        W = int(rng.integers(max(1, S - 2 * pad), 90 if big else 24))
+        if rng.random() < 0.4:
+            W = max(4, (W // 4) * 4)
+        if H + 2 * pad < R or W + 2 * pad < S:
+            continue
+        N = int(rng.integers(1, 3 if big else 12))
+        C, M = int(rng.integers(1, 5 if big else 9)), int(rng.integers(1, 6 if big else 12))
+        L = wl.custom_layer(N, C, H, W, M, R, S, stride, pad, float(rng.choice([0.0, 0.3, 0.6, 0.9])),
+                            seed=9000 + it, dist="normal")
+        tune = {}
+        if rng.random() < 0.7:
+            tune["K"], tune["Q"] = [(1, 1), (1, 2), (2, 1), (2, 2), (4, 1), (4, 2), (8, 1)][int(rng.integers(0, 7))]
+        if rng.random() < 0.5:
+            tune["WM"] = int(rng.integers(1, 5))
+        if rng.random() < 0.5:
+            tune["CC"] = int(rng.integers(1, C + 1))
+        if rng.random() < 0.4:
+            tune["NB"] = int(rng.integers(1, N + 1))
+        elif rng.random() < 0.4:
+            tune["TH"] = int(rng.integers(1, L.spec.E + 1))
+        if rng.random() < 0.3:
+            tune["CS"] = int(rng.integers(1, 4))
+        flags = int(rng.integers(0, 4))
+        print("sconv tiled random", it, (N, C, H, W, M, R, S, stride, pad), tune, flags, flush=True)
+        try:
+            got = DeviceLayer(esc, L, tuning=tune or None).forward_tiled(flags)
+        except esc.EscoinError as e:
+            assert e.code in (esc.ERANGE, esc.EINVAL)
+            continue
+        ref, bound = oracle_full(oracle, L, flags)
+        assert_within_bound(got, ref, bound, f"random case {it}")
+        done += 1
+    assert done >= 150
+
+
 # ------------------------------------------------------------------ the paper-shaped layers
 FULL_WHOLE = ["A1b1", "A2b1", "A3b1"]                      # oracle computes every element quickly
 FULL_SAMPLED = ["R56", "R28", "R14", "R7", "R56s2", "G1", "G3", "G5", "A2b64", "S80", "S95",
