@@ -163,11 +163,13 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
     h->CS = std::max(1, std::min(h->CS, h->n_chunks));
     h->n_mgroups = ceil_div(d.M, h->K * h->WM);
     // two window buffers (the next chunk is fetched while the current one is consumed) plus a
-    // zeroed tail that lanes past the last plane may read
+    // zeroed tail
     const long long buf = (long long)h->n_phases * h->CC * h->NB * h->plane_stride;
     if (buf * 8 > kLdsBudgetBytes) return ESCOIN_ERANGE;
     h->buf_floats = (int)buf;
-    h->tail_floats = round_up(g->max_aoff + 16, 4);
+    // Lanes past the tile's last group still read: at most one group past it in a wave's first
+    // run and 62 groups further for each following run of that wave.
+    h->tail_floats = round_up(g->max_aoff + 16 + 4 * kRunLanes * (h->Q - 1), 4);
     if ((long long)h->NB * d.C * d.H * d.W >= (long long)INT32_MAX) return ESCOIN_ERANGE;
     if (h->WQ * h->WM > 16) return ESCOIN_ERANGE;  // at most 1024 threads per workgroup
     return ESCOIN_OK;

@@ -108,11 +108,12 @@ __device__ __forceinline__ Batch<B> read_batch(const char* lds_bytes, int addr) 
 // holds a single image (62 groups of 16 bytes)
 constexpr int kRunStrideBytes = 62 * 16;
 
-// CONTIG: the workgroup's tile holds one image, so a lane's groups in consecutive position runs
-// are kRunStrideBytes apart and the second LDS read needs no address arithmetic of its own.
+// A tile's groups are consecutive in LDS whatever image they belong to, so a lane's groups in
+// consecutive position runs are kRunStrideBytes apart and the second LDS read of a record needs no
+// address arithmetic of its own (an immediate offset).
 // VW: input words per staging load (4: the plan dealt the window words in runs of four
 // consecutive, 16-byte aligned input words and the input pointer is 16-byte aligned; 1: any plan).
-template <int K, int Q, int B, bool CONTIG, int VW>
+template <int K, int Q, int B, int VW>
 __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     char* const lds_bytes = (char*)lds;
@@ -251,8 +252,7 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
                 const int at = base0 + bufb + (int)cur.w[u >> 1][(u & 1) * 2];
 #pragma unroll
                 for (int q = 0; q < Q; ++q)
-                    x[u][q] = *(const f4*)__builtin_assume_aligned(
-                        lds_bytes + (CONTIG ? at + q * kRunStrideBytes : at + (base_bytes[q] - base0)), 16);
+                    x[u][q] = *(const f4*)__builtin_assume_aligned(lds_bytes + at + q * kRunStrideBytes, 16);
             }
 #pragma unroll
             for (int u = 0; u < B; ++u)
@@ -368,23 +368,15 @@ typedef void (*TiledKernel)(const TiledArgs);
 // nine registers less; the ones the layers with W % 4 == 0 of the bundled workloads use).
 #define ESCOIN_TILED_WIDE_STAGING(X) X(1, 1, 2) X(2, 1, 2) X(4, 1, 2) X(2, 2, 2) X(4, 2, 2)
 
-template <int K, int Q, int B, int VW>
-TiledKernel instance(bool contig) {
-    if constexpr (Q > 1) {
-        if (contig) return sconv_tiled_kernel<K, Q, B, true, VW>;
-    }
-    return sconv_tiled_kernel<K, Q, B, false, VW>;
-}
-
-TiledKernel pick(int K, int Q, int B, bool contig, bool wide_staging) {
+TiledKernel pick(int K, int Q, int B, bool wide_staging) {
     if (wide_staging) {
 #define ESCOIN_PICK(KK, QQ, BB) \
-    if (K == KK && Q == QQ && B == BB) return instance<KK, QQ, BB, 4>(contig);
+    if (K == KK && Q == QQ && B == BB) return sconv_tiled_kernel<KK, QQ, BB, 4>;
         ESCOIN_TILED_WIDE_STAGING(ESCOIN_PICK)
 #undef ESCOIN_PICK
     }
 #define ESCOIN_PICK(KK, QQ, BB) \
-    if (K == KK && Q == QQ && B == BB) return instance<KK, QQ, BB, 1>(contig);
+    if (K == KK && Q == QQ && B == BB) return sconv_tiled_kernel<KK, QQ, BB, 1>;
     ESCOIN_TILED_VARIANTS(ESCOIN_PICK)
 #undef ESCOIN_PICK
     return nullptr;
@@ -427,7 +419,7 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
         h.stride != d.stride || h.pad != d.pad || h.E != d.E || h.F != d.F)
         return ESCOIN_EINVAL;
     // 16-byte staging loads need the plan's runs of four words and a 16-byte aligned input
-    TiledKernel kern = pick(h.K, h.Q, h.B, h.NB == 1, h.VW == 4 && ((uintptr_t)d_in & 15) == 0);
+    TiledKernel kern = pick(h.K, h.Q, h.B, h.VW == 4 && ((uintptr_t)d_in & 15) == 0);
     if (!kern) return ESCOIN_EINVAL;
     const int threads = 64 * h.WQ * h.WM;
     if (threads > 1024 || threads <= 0) return ESCOIN_EINVAL;

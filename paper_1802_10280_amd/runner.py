@@ -63,9 +63,8 @@ class LayerRunner:
     def sconv_kernel_name(self):
         if self.path == "tiled":
             h = self.plan_info
-            contig = "true" if (h["Q"] > 1 and h["NB"] == 1) else "false"
             vw = h["VW"] if self.d_in.data_ptr() % 16 == 0 else 1
-            return f"sconv_tiled_kernel<{h['K']}, {h['Q']}, {h['B']}, {contig}, {vw}>"
+            return f"sconv_tiled_kernel<{h['K']}, {h['Q']}, {h['B']}, {vw}>"
         return "sconv_direct_kernel"
 
     def run(self):

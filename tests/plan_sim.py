@@ -62,6 +62,20 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
                 # both neighbours hold the adjacent groups
                 assert lanes[r, l - 1, 0] == b - 4 and lanes[r, l + 1, 0] == b + 4
     assert (owned == 1).all(), "lane table must own every position once"
+    # The kernel takes a wave's first run from the table and finds the lanes' groups of its
+    # following runs 62 groups further: same thing for every lane that owns outputs or lends
+    # data, and in bounds (window buffer + zeroed tail) for the idle ones.
+    max_aoff_words = int(rec_off.max()) // 4 % (NB * ps) + 4 if len(rec_off) else 4
+    for wq in range(WQ):
+        first = lanes[wq * Q, :, 0].astype(np.int64)
+        for q in range(1, Q):
+            kernel_base = first + 62 * 4 * q
+            table = lanes[wq * Q + q]
+            live = (table[:, 1] >= 0)
+            live[:-1] |= table[1:, 1] >= 0        # lends to the next lane
+            live[1:] |= table[:-1, 1] >= 0        # lends to the previous lane
+            assert (kernel_base[live] == table[live, 0]).all(), "runs of a wave are not 62 groups apart"
+            assert kernel_base.max() + max_aoff_words + 4 <= (NB * ps) + h["tail_floats"]
 
     out = np.full((N, M, h["E"] * h["F"]), np.nan)
     xf = x.reshape(N, C, H * W).astype(np.float64)
