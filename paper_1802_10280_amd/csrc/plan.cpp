@@ -438,10 +438,12 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
             }
         }
     }
-    // Input order (row, column): with full-width tiles every row is complete, so when W is a
-    // multiple of 4 the words of a tile come in runs of 4 consecutive, 16-byte aligned input
-    // words that one wide load can fetch (if the kernel variant has such loads).
-    h.VW = (d.W % 4 == 0 && tiled_wide_staging_exists(h.K, h.Q, h.B)) ? 4 : 1;
+    // Input order (row, column): with full-width tiles every row is complete, so the words of
+    // a tile are one stretch of each input plane.  When planes are whole 16-byte groups and the
+    // stretch starts on one, it splits into runs of 4 consecutive, 16-byte aligned input words
+    // (a run may span two rows) that one wide load can fetch, if the kernel variant has such
+    // loads.  The loop below checks the alignment tile by tile.
+    h.VW = ((d.H * d.W) % 4 == 0 && tiled_wide_staging_exists(h.K, h.Q, h.B)) ? 4 : 1;
     for (auto& v : items) {
         std::stable_sort(v.begin(), v.end(), [](const WindowWord& a, const WindowWord& b) { return a.src < b.src; });
         for (size_t i = 0; i < v.size() && h.VW > 1; ++i)
