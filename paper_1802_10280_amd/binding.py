@@ -206,7 +206,7 @@ PLAN_HEADER_FIELDS = (
      "lds_bytes", "nnz", "n_records"],
     ["off_items", "off_lanes", "off_dst_lut", "off_perm", "off_blk", "off_seg", "off_rec",
      "total_bytes"],
-    ["CS", "pitch1", "VW"])
+    ["CS", "pitch1", "VW", "WW"])
 
 
 def plan_header(plan: np.ndarray) -> dict:

@@ -552,6 +552,7 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     // The (channel, image, word) triples of a chunk are dealt to the threads round-robin, so a
     // wave's loads of one slot touch consecutive input words.
     StageSlot* slots = (StageSlot*)(base + h.off_items);
+    bool wide_commit = h.VW == 4;
     int32_t* dst = (int32_t*)(base + h.off_dst_lut);
     for (int t = 0; t < h.n_tiles; ++t) {
         const int h0 = t * h.TH;
@@ -579,12 +580,25 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
                 }
                 slots[((size_t)t * kMaxItemsPerThread + j) * threads + tid] = sl;
             }
+        // can a run be committed with one 16-byte LDS write?
+        if (h.VW == 4)
+            for (int j = 0; j < kMaxItemsPerThread; j += 4)
+                for (int tid = 0; tid < threads; ++tid) {
+                    const StageSlot* q = &slots[((size_t)t * kMaxItemsPerThread + j) * threads + tid];
+                    if (q[0].src < 0) continue;
+                    for (int i = 0; i < 4; ++i) {
+                        const StageSlot& w = q[(size_t)i * threads];
+                        if (w.src < 0 || w.key != q[0].key + 4u * i || (q[0].key & 15u)) wide_commit = false;
+                    }
+                }
         for (int p = 0; p < h.P4; ++p) {
             const int hh = p / h.pitch, w = (p - hh * h.pitch) % h.pitch1;  // column inside its image
             dst[(size_t)t * h.P4 + p] =
                 (hh < h.TH && h0 + hh < d.E && w < d.F) ? (h0 + hh) * d.F + w : -1;
         }
     }
+    h.WW = wide_commit ? 4 : 1;
+    std::memcpy(base, &h, sizeof(h));  // the header once more, now with WW
     std::memcpy(base + h.off_lanes, lanes.data(), lanes.size() * sizeof(LaneSlot));
     std::memcpy(base + h.off_perm, perm.data(), perm.size() * 4);
     std::memcpy(base + h.off_blk, blk.data(), blk.size() * 4);

@@ -11,7 +11,7 @@
 namespace escoin {
 
 constexpr uint32_t kPlanMagic = 0x4E4C5045u;  // "EPLN"
-constexpr uint32_t kPlanVersion = 11;
+constexpr uint32_t kPlanVersion = 12;
 constexpr int kMaxPhases = 16;          // stride*stride phase planes
 constexpr int kClasses = 4;             // alignment classes of a tap: (LDS offset) mod 4
 constexpr int kMaxItemsPerThread = 12;  // staged input words per thread and chunk
@@ -71,7 +71,9 @@ struct PlanHeader {
     int32_t pitch1;  // columns of one image inside a row of `pitch` floats (pitch = NB * pitch1)
     int32_t VW;      // a thread's staging slots come in runs of VW (4 or 1) consecutive input
                      // words whose first is VW-word aligned inside the input tensor
-    uint32_t reserved[5];
+    int32_t WW;      // 4: every run of VW = 4 words also lands on 4 consecutive, 16-byte aligned LDS
+                     // words, so one 16-byte LDS write commits it; else 1
+    uint32_t reserved[4];
 };
 
 }  // namespace escoin

@@ -43,7 +43,7 @@ struct TiledArgs {
     const uint32_t* seg;
     const uint32_t* rec;
     int N, C, HW, M, EF;
-    int WM, WQ, CC, NB, CS;
+    int WM, WQ, CC, NB, CS, WW;
     int n_tiles, n_mgroups, n_chunks, n_in_tiles;
     int plane_stride, P4, n_items, buf_floats, tail_floats, rec_buf_bytes;
     uint32_t flags;
@@ -204,6 +204,16 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
     auto commit = [&](int ch, int buf) {
         const int ccur = min(a.CC, a.C - ch * a.CC);
         char* const win = lds_bytes + buf * win_bytes;
+        if (VW == 4 && a.WW == 4) {  // every run lands on 16 aligned, consecutive LDS bytes
+#pragma unroll
+            for (int r = 0; r < kRuns; ++r)
+                if (st_src[r] >= 0 && (int)(st_key[4 * r] >> 24) < ccur) {
+                    f4 v;
+                    v[0] = st_val[4 * r]; v[1] = st_val[4 * r + 1]; v[2] = st_val[4 * r + 2]; v[3] = st_val[4 * r + 3];
+                    *(f4*)__builtin_assume_aligned(win + (st_key[4 * r] & 0xFFFFFF), 16) = v;
+                }
+            return;
+        }
 #pragma unroll
         for (int j = 0; j < kMaxItemsPerThread; ++j)
             if (st_src[j / VW] >= 0 && (int)(st_key[j] >> 24) < ccur)
@@ -426,7 +436,7 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     // the kernel's index arithmetic relies on these plan invariants
     if (h.P4 % 4 || h.plane_stride % 4 || (long long)h.P4 > (long long)h.NB * h.plane_stride || h.NB < 1 || h.CC < 1 ||
         h.WQ < 1 || h.WM < 1 || h.tail_floats % 4 || h.rec_buf_bytes % 16 || h.front < 4 ||
-        h.n_phases < 1 || h.n_phases > kMaxPhases || (h.VW != 1 && h.VW != 4) || h.CS < 1 || h.CS > h.n_chunks ||
+        h.n_phases < 1 || h.n_phases > kMaxPhases || (h.VW != 1 && h.VW != 4) || (h.WW != 1 && h.WW != 4) || (h.WW == 4 && h.VW != 4) || h.CS < 1 || h.CS > h.n_chunks ||
         h.buf_floats != h.n_phases * h.CC * h.NB * h.plane_stride ||
         (long long)h.n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads ||
         (long long)h.buf_floats * 4 >= (1 << 24) ||
@@ -444,7 +454,7 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     a.seg = (const uint32_t*)(base + h.off_seg);
     a.rec = (const uint32_t*)(base + h.off_rec);
     a.N = d.N; a.C = d.C; a.HW = d.H * d.W; a.M = d.M; a.EF = d.E * d.F;
-    a.WM = h.WM; a.WQ = h.WQ; a.CC = h.CC; a.NB = h.NB; a.CS = h.CS;
+    a.WM = h.WM; a.WQ = h.WQ; a.CC = h.CC; a.NB = h.NB; a.CS = h.CS; a.WW = h.WW;
     a.n_tiles = h.n_tiles; a.n_mgroups = h.n_mgroups; a.n_chunks = h.n_chunks;
     const long long n_in_tiles = (long long)h.n_tiles * ((d.N + h.NB - 1) / h.NB);
     const long long blocks = (n_in_tiles * h.n_mgroups * h.CS + 7) / 8 * 8;
