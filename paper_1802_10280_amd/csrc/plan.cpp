@@ -452,6 +452,18 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     size_t n_items = 0;
     for (auto& v : items) n_items = std::max(n_items, v.size());
     if (n_items % h.VW) h.VW = 1;
+    // Planes that are not whole 16-byte groups (7x7, 13x13): when a tile takes whole planes, the
+    // words of one image and chunk are still one stretch of memory, (channel, row, column).  With
+    // C and CC multiples of 4 that stretch starts 16-byte aligned and ends on a run boundary in
+    // every chunk (also the shorter last one), so it splits into runs of 4 the same way; a run
+    // may then span two channels.
+    bool flat_runs = false;
+    if (h.VW == 1 && tiled_wide_staging_exists(h.K, h.Q, h.B) && h.n_tiles == 1 && d.C % 4 == 0 &&
+        h.CC % 4 == 0 && (int)items[0].size() == d.H * d.W) {
+        flat_runs = true;
+        for (size_t i = 0; i < items[0].size(); ++i) flat_runs = flat_runs && items[0][i].src == (int)i;
+        if (flat_runs) h.VW = 4;
+    }
     n_items = std::max<size_t>(n_items, 1);
     if ((long long)n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads) return ESCOIN_ERANGE;
     h.n_items = (int32_t)n_items;
@@ -559,7 +571,8 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
         // Runs of VW words are dealt to the threads round-robin (a wave's loads of one slot
         // touch consecutive runs); a thread's slots j*VW .. j*VW+VW-1 hold one run.
         const int n_runs = h.n_items / h.VW;
-        const long long total_runs = (long long)n_runs * h.CC * h.NB;
+        const int flat_per_image = h.CC * h.n_items / 4;  // runs of one image's stretch
+        const long long total_runs = flat_runs ? (long long)flat_per_image * h.NB : (long long)n_runs * h.CC * h.NB;
         for (int j = 0; j < kMaxItemsPerThread; ++j)
             for (int tid = 0; tid < threads; ++tid) {
                 StageSlot sl;
@@ -567,9 +580,18 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
                 sl.key = 0;
                 const long long run = tid + (long long)(j / h.VW) * threads;
                 if (run < total_runs) {
-                    const int cn = (int)(run / n_runs);
-                    const int i = (int)(run - (long long)cn * n_runs) * h.VW + j % h.VW;
-                    const int cl = cn / h.NB, nl = cn - cl * h.NB;
+                    int cl, nl, i;
+                    if (flat_runs) {
+                        nl = (int)(run / flat_per_image);
+                        const int f = (int)(run - (long long)nl * flat_per_image) * 4 + j % 4;
+                        cl = f / h.n_items;
+                        i = f - cl * h.n_items;
+                    } else {
+                        const int cn = (int)(run / n_runs);
+                        i = (int)(run - (long long)cn * n_runs) * h.VW + j % h.VW;
+                        cl = cn / h.NB;
+                        nl = cn - cl * h.NB;
+                    }
                     if ((size_t)i < items[t].size()) {
                         sl.src = (nl * d.C + cl) * (d.H * d.W) + items[t][i].src;
                         // channel cl's plane set, then image nl's columns inside the wide rows
@@ -675,6 +697,9 @@ int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_
     h.CS = auto_cs ? 1 : tuning->CS;
     for (;;) {
         if (auto_cs) choose_split(d, auto_cc, &h);
+        // planes that are not whole 16-byte groups can still be staged with 16-byte loads when
+        // the chunk is a multiple of 4 channels
+        if (auto_cc && (d.H * d.W) % 4 != 0 && d.C % 4 == 0 && h.CC >= 8) h.CC -= h.CC % 4;
         rc = build_plan_once(d, rowptr, stretched, value, h, out, out_bytes, bytes);
         if (rc != ESCOIN_ERANGE) return rc;
         if (auto_cc && h.CC > 1) {

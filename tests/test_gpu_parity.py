@@ -93,6 +93,8 @@ TUNINGS = [
     dict(K=4, Q=1, B=4, WM=5, CC=4, TH=4),
     dict(K=1, Q=1, B=2, WM=4, CC=2, CS=3),          # channels split over 3 workgroups, atomics
     dict(K=2, Q=2, B=2, WM=2, CC=1, CS=2, TH=7),
+    dict(K=1, Q=1, B=2, WM=3, CC=4, NB=3),          # 16-byte staging runs across channels where C % 4 == 0
+    dict(K=2, Q=2, B=2, WM=2, CC=8, NB=2),
 ]
 
 

@@ -30,6 +30,8 @@ CASES = [
     ((9, 6, 5, 6, 7, 3, 3, 1, 1, 0.5), dict(NB=4)),                  # four images side by side, ragged last group
     ((5, 3, 6, 5, 4, 3, 3, 2, 1, 0.5), dict(NB=2)),                  # stride 2 with two images per tile
     ((5, 6, 11, 1, 10, 4, 1, 1, 3, 0.0), dict(CC=3, NB=3)),          # output rows wider than W + pad
+    ((6, 8, 7, 7, 9, 3, 3, 1, 1, 0.6), dict(K=1, NB=4, CC=4)),       # 16-byte staging runs across channels
+    ((3, 12, 13, 13, 7, 3, 3, 1, 1, 0.6), dict(K=2, Q=2, NB=2, CC=8)),  # the same with a shorter last chunk
 ]
 
 
@@ -44,6 +46,8 @@ def test_plan_replay_matches_oracle(oracle, cfg, tune):
     assert h["total_bytes"] == plan.nbytes and h["nnz"] == L.nnz
     for k, v in tune.items():
         assert h[k] == v, (k, h[k], v)
+    if cfg[:4] in ((6, 8, 7, 7), (3, 12, 13, 13)):
+        assert h["VW"] == 4                      # the flat (channel, row, column) runs
     got = simulate(plan, L.input, M)
     Wd = oracle.csr_to_dense(M, C, R, S, L.rowptr, L.colidx, L.value)
     ref, bound = oracle.conv(L.input, Wd, stride, pad)
