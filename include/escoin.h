@@ -137,8 +137,9 @@ int escoin_sconv_plan_size(const escoin_conv_desc *desc, const int32_t *rowptr,
                            size_t *plan_bytes);
 
 /* Builds the plan into caller-owned host memory `plan` (plan_bytes from the size query, else
- * ESCOIN_ESIZE).  The plan does not depend on N.  The caller then copies the blob verbatim to
- * device memory (256-byte aligned) and keeps the host copy for escoin_sconv_forward_tiled.
+ * ESCOIN_ESIZE).  A plan is valid for every batch size (only C, H, W, M, R, S, stride and pad are
+ * checked at launch); desc->N only guides the default tiling.  The caller then copies the blob
+ * verbatim to device memory (256-byte aligned) and keeps the host copy for escoin_sconv_forward_tiled.
  * ESCOIN_EINVAL if an offset is not one weight stretching can produce for this desc. */
 int escoin_sconv_plan_build(const escoin_conv_desc *desc, const int32_t *rowptr,
                             const int32_t *colidx_stretched, const float *value,

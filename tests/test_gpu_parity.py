@@ -290,6 +290,29 @@ def test_tiled_random_layers_and_tilings(oracle):
     assert done >= 150
 
 
+def test_tiled_plan_serves_other_batch_sizes(oracle):
+    """A plan built for one batch size runs any other: here 8 -> 5 and 8 -> 11 images, with
+    several images per tile so that the last tile is ragged."""
+    import torch
+    print("sconv tiled plan reuse across batch sizes", flush=True)
+    L8 = wl.custom_layer(8, 8, 7, 7, 6, 3, 3, 1, 1, 0.6, seed=41, dist="normal")
+    d8 = esc.desc_of(L8.spec)
+    st = esc.escoin_sconv_pack(d8, L8.rowptr, L8.colidx)
+    plan = esc.escoin_sconv_plan_build(d8, L8.rowptr, st, L8.value, esc.make_tuning(NB=3))
+    d_plan = to_dev(plan)
+    Wd = oracle.csr_to_dense(6, 8, 3, 3, L8.rowptr, L8.colidx, L8.value)
+    rng = np.random.default_rng(3)
+    for n in (5, 11):
+        x = rng.random((n, 8, 7, 7), dtype=np.float32)
+        d = esc.make_desc(n, 8, 7, 7, 6, 3, 3, 1, 1)
+        d_in = to_dev(x)
+        d_out = torch.full((n, 6, 7, 7), float("nan"), dtype=torch.float32, device="cuda")
+        esc.escoin_sconv_forward_tiled(d, plan, d_plan, d_in, d_out, None, 0)
+        torch.cuda.synchronize()
+        ref, bound = oracle.conv(x, Wd, 1, 1)
+        assert_within_bound(d_out.cpu().numpy(), ref, bound, f"batch {n}")
+
+
 # ------------------------------------------------------------------ the paper-shaped layers
 FULL_WHOLE = ["A1b1", "A2b1", "A3b1"]                      # oracle computes every element quickly
 FULL_SAMPLED = ["R56", "R28", "R14", "R7", "R56s2", "G1", "G3", "G5", "A2b64", "S80", "S95",
