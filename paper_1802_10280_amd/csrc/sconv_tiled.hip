@@ -224,7 +224,8 @@ __global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
     fetch(cs, 0);
     // The frame of zeros never changes: clear the window buffers and the tail once; from here
     // on only words that hold input are rewritten, chunk after chunk.
-    for (int i = tid; i < 2 * a.buf_floats + a.tail_floats; i += nthreads) lds[i] = 0.0f;
+    for (int i = 4 * tid; i < 2 * a.buf_floats + a.tail_floats; i += 4 * nthreads)  // both are multiples of 4
+        *(f4*)__builtin_assume_aligned(&lds[i], 16) = (f4)(0.0f);
     __syncthreads();
     commit(cs, 0);
     __builtin_amdgcn_s_waitcnt(0);  // this wave's record copies have landed
