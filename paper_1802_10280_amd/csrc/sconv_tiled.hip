@@ -114,7 +114,7 @@ constexpr int kRunStrideBytes = 62 * 16;
 // VW: input words per staging load (4: the plan dealt the window words in runs of four
 // consecutive, 16-byte aligned input words and the input pointer is 16-byte aligned; 1: any plan).
 template <int K, int Q, int B, int VW>
-__global__ __launch_bounds__(1024) void sconv_tiled_kernel(const TiledArgs a) {
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) void sconv_tiled_kernel(const TiledArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     char* const lds_bytes = (char*)lds;
     const int tid = threadIdx.x;
