@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-images", type=int, default=0,
                     help="images per layer for the oracle sample (0 = auto, about 10-30 s)")
+    ap.add_argument("--others", action="store_true",
+                    help="after the timed workload, also time the other bundled workloads (50 steps "
+                         "each) and report their GFLOP/s under `other_workloads`")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a few launches of a plain copy of known size "
@@ -180,6 +183,31 @@ def main():
         "roofline": roofline,
         "layers": rows,
     }
+
+    if args.others:
+        # context only: the same measurement, shorter, on the other bundled workloads
+        del runners
+        others = {}
+        for w, ns in wl.CONFIG_LAYERS.items():
+            if w == args.workload:
+                continue
+            ls = [wl.make_layer(n) for n in ns]
+            rs = [LayerRunner(L, path=args.path, flags=args.flags) for L in ls]
+            fl = sum(2.0 * L.nnz * L.spec.E * L.spec.F * L.spec.N for L in ls)
+            for _ in range(5):
+                for r in rs:
+                    r.run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(50):
+                for r in rs:
+                    r.run()
+            torch.cuda.synchronize()
+            t = (time.perf_counter() - t0) / 50
+            others[w] = {"gflops": round(fl / t / 1e9, 1), "ms_per_step": round(t * 1e3, 4),
+                         "layers": ",".join(ns)}
+            del rs, ls
+        out["other_workloads"] = others
 
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(layers, args.cpu_images)
