@@ -122,12 +122,17 @@ typedef struct escoin_sconv_tuning {
     int32_t K;  /* output channels accumulated per wave: 1, 2, 4 or 8               */
     int32_t Q;  /* 16-byte position groups per lane, 1 or 2                         */
     int32_t B;  /* nonzeros per record batch, 2 or 4 (not every K/Q/B mix exists)   */
-    int32_t WM; /* waves per workgroup along the output-channel axis                */
+    int32_t WM; /* waves per workgroup along the output-channel axis (WS included)  */
     int32_t CC; /* input channels staged per LDS chunk                              */
     int32_t NB; /* images per workgroup                                             */
     int32_t TH; /* output rows per tile                                             */
     int32_t CS; /* workgroups sharing one output tile, each taking every CS-th      */
                 /* channel chunk and adding its partial sums with float atomics     */
+    int32_t WS; /* every output channel's nonzeros are split over at least WS waves */
+                /* of a workgroup, whose partial sums are added in LDS (rows much   */
+                /* longer than a wave's share are split further by the library)     */
+    int32_t CC0;/* input channels of the first chunk, <= CC (a short first chunk    */
+                /* lets the arithmetic start before the whole window has arrived)   */
 } escoin_sconv_tuning;
 
 /* Bytes the plan blob needs.  Host; rowptr / colidx_stretched as returned by

@@ -23,7 +23,7 @@ class escoin_conv_desc(ctypes.Structure):
 
 
 class escoin_sconv_tuning(ctypes.Structure):
-    _fields_ = [(k, ctypes.c_int32) for k in ("K", "Q", "B", "WM", "CC", "NB", "TH", "CS")]
+    _fields_ = [(k, ctypes.c_int32) for k in ("K", "Q", "B", "WM", "CC", "NB", "TH", "CS", "WS", "CC0")]
 
 
 class EscoinError(RuntimeError):
@@ -159,7 +159,7 @@ def escoin_sconv_forward(desc, d_rowptr, d_colidx_stretched, d_value, d_padded, 
 
 
 def make_tuning(**kw):
-    """Tiling knobs for the plan (K, Q, B, WM, CC, NB, TH); omitted fields are chosen by the
+    """Tiling knobs for the plan (K, Q, B, WM, CC, NB, TH, CS, WS, CC0); omitted fields are chosen by the
     library.  Returns None when nothing is given."""
     if not kw:
         return None
@@ -206,7 +206,7 @@ PLAN_HEADER_FIELDS = (
      "lds_bytes", "nnz", "n_records"],
     ["off_items", "off_lanes", "off_dst_lut", "off_perm", "off_blk", "off_seg", "off_rec",
      "total_bytes"],
-    ["CS", "pitch1", "VW", "WW"])
+    ["CS", "pitch1", "VW", "WW", "WS", "CC0", "zero_floats", "max_regions"])
 
 
 def plan_header(plan: np.ndarray) -> dict:

@@ -140,7 +140,12 @@ int build_geometry(const Dims& d, int pitch, int front, Geometry* g) {
     return ESCOIN_OK;
 }
 
-// Fills every derived field of `h` from the knobs K, Q, B, WM, CC, NB, TH (already set).
+// Channel chunks: the first one holds CC0 channels, the others CC (the last one what is left).
+inline int chunk_of(const PlanHeader& h, int c) { return c < h.CC0 ? 0 : 1 + (c - h.CC0) / h.CC; }
+inline int chunk_start(const PlanHeader& h, int ch) { return ch == 0 ? 0 : h.CC0 + (ch - 1) * h.CC; }
+
+// Fills every derived field of `h` from the knobs K, Q, B, WM, WS, CC, CC0, NB, TH (already set).
+// n_mgroups is the count before long rows are split (build_plan_once may add groups).
 int derive(const Dims& d, PlanHeader* h, Geometry* g) {
     h->pitch = wide_pitch(d, h->NB);
     h->pitch1 = image_pitch(d, h->NB);
@@ -159,12 +164,19 @@ int derive(const Dims& d, PlanHeader* h, Geometry* g) {
     const int runs = std::max(1, ceil_div(entries - 2, kRunLanes));
     h->WQ = ceil_div(runs, h->Q);
     h->CC = std::min(h->CC, d.C);
-    h->n_chunks = ceil_div(d.C, h->CC);
+    // the staging key holds the channel inside the chunk in 14 bits
+    if (h->CC > kMaxChunkChannels) return ESCOIN_ERANGE;
+    h->CC0 = h->CC0 > 0 ? std::min(h->CC0, h->CC) : h->CC;
+    h->n_chunks = d.C <= h->CC0 ? 1 : 1 + ceil_div(d.C - h->CC0, h->CC);
     h->CS = std::max(1, std::min(h->CS, h->n_chunks));
-    h->n_mgroups = ceil_div(d.M, h->K * h->WM);
+    h->WS = std::max(1, std::min(h->WS, h->WM));
+    h->n_mgroups = (int)std::min<long long>(INT32_MAX, ((long long)d.M * h->WS + (long long)h->K * h->WM - 1) / ((long long)h->K * h->WM));
+    // Behind the channel planes every window buffer keeps a stretch nothing writes: a record
+    // that only fills up a batch points there and multiplies zeros, whatever the input holds.
+    h->zero_floats = round_up(h->P4 + 16, 4);
     // two window buffers (the next chunk is fetched while the current one is consumed) plus a
     // zeroed tail
-    const long long buf = (long long)h->n_phases * h->CC * h->NB * h->plane_stride;
+    const long long buf = (long long)h->n_phases * h->CC * h->NB * h->plane_stride + h->zero_floats;
     if (buf * 8 > kLdsBudgetBytes) return ESCOIN_ERANGE;
     h->buf_floats = (int)buf;
     // Lanes past the tile's last group still read: at most one group past it in a wave's first
@@ -258,6 +270,8 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
     h->TH = (t && t->TH > 0) ? t->TH : bestTH;
     h->NB = (t && t->NB > 0) ? t->NB : ((t && t->TH > 0 && t->TH < d.E) ? 1 : bestNB);
     h->WM = (t && t->WM > 0) ? t->WM : bestWM;
+    h->WS = (t && t->WS > 0) ? t->WS : 1;
+    h->CC0 = (t && t->CC0 > 0) ? t->CC0 : 0;
     if (t && t->CC > 0) {
         h->CC = t->CC;
     } else {
@@ -267,7 +281,7 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
         const int lds_target = 128 * 1024;  // the rest holds the two record buffers
         if (derive(d, &probe, &g) == ESCOIN_OK) {
             const int per_c = 2 * probe.n_phases * probe.NB * probe.plane_stride * 4;
-            h->CC = std::max(1, std::min(d.C, lds_target / per_c));
+            h->CC = std::max(1, std::min(d.C, (lds_target - 8 * probe.zero_floats) / per_c));
             h->CC = ceil_div(d.C, ceil_div(d.C, h->CC));  // equalise the chunks
         } else {
             h->CC = 1;
@@ -325,95 +339,192 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
         const int rem = off - c * plane_in;
         const int r = rem / d.Wp, s = rem - r * d.Wp;
         if (r >= d.R || s >= d.S) return ESCOIN_EINVAL;  // not an offset weight stretching makes
-        const int chunk = c / h.CC, cl = c - chunk * h.CC;
+        const int chunk = chunk_of(h, c), cl = c - chunk_start(h, chunk);
         const int tap = r * d.S + s;
         const long long fl = ((long long)g.tap_phase[tap] * h.CC + cl) * chan_stride + g.tap_aoff[tap];
-        nz_chunk[j] = chunk;
+        // An explicit zero contributes nothing to any sum (the definition skips it as well), so
+        // it gets no record: chunk -1.  Without values (size query) every entry counts.
+        nz_chunk[j] = (value && value[j] == 0.0f) ? -1 : chunk;
         nz_class[j] = g.tap_class[tap];
         nz_off[j] = (uint32_t)(fl * 4);
     }
-
-    // ---- rows -> bins (one bin = the K accumulator rows of one wave), balanced by nnz: rows in
-    // order of decreasing length each go to the bin with the least work so far that still has
-    // a free accumulator row.  Consecutive bins belong to different workgroups.
-    const int bins = h.n_mgroups * h.WM;
-    std::vector<int> order(d.M);
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
-        return rowptr[a + 1] - rowptr[a] > rowptr[b + 1] - rowptr[b];
-    });
-    std::vector<int32_t> perm((size_t)bins * h.K, -1);
-    {
-        std::vector<long long> load(bins, 0);
-        std::vector<int> used(bins, 0);
-        for (int i = 0; i < d.M; ++i) {
-            int best = -1;
-            for (int b = 0; b < bins; ++b)
-                if (used[b] < h.K && (best < 0 || load[b] < load[best])) best = b;
-            const int mg = best % h.n_mgroups, wm = best / h.n_mgroups;
-            perm[((size_t)mg * h.WM + wm) * h.K + used[best]] = order[i];
-            load[best] += rowptr[order[i] + 1] - rowptr[order[i]] + 1;
-            used[best]++;
-        }
-    }
-    // Per row, chunk and class: how many nonzeros, hence how many record batches.
+    // Per row, chunk and class: how many nonzeros.
     const int B = h.B;
     std::vector<int> rcc((size_t)d.M * h.n_chunks * kClasses, 0);
+    std::vector<long long> nnz_row(d.M, 0);
+    long long nnz_total = 0;
     for (int m = 0; m < d.M; ++m)
         for (int j = rowptr[m]; j < rowptr[m + 1]; ++j)
-            rcc[((size_t)m * h.n_chunks + nz_chunk[j]) * kClasses + nz_class[j]]++;
-    // The waves of a workgroup meet at a barrier after every chunk, so a workgroup's time is
-    // the sum over chunks of its slowest wave.  Inside each workgroup the rows are dealt to the
-    // waves once more, longest first, each to the wave (with a free accumulator row) where it
-    // raises that sum the least.
-    if (h.WM > 1 && h.n_chunks > 1) {
-        std::vector<int> rows, batches((size_t)h.K * h.WM * h.n_chunks);
-        std::vector<int> wave_load((size_t)h.WM * h.n_chunks), peak(h.n_chunks), wave_rows(h.WM);
+            if (nz_chunk[j] >= 0) {
+                rcc[((size_t)m * h.n_chunks + nz_chunk[j]) * kClasses + nz_class[j]]++;
+                nnz_row[m]++;
+                nnz_total++;
+            }
+
+    // ---- output channels -> accumulator rows.  A wave has K accumulator rows; a channel takes
+    // `parts` of them, in different waves of one workgroup, each with a share of its nonzeros
+    // (the partial sums meet in LDS after the last chunk).  Every channel gets at least WS
+    // parts; a channel whose nonzeros exceed a wave's fair share by more than a quarter gets
+    // more, as long as accumulator rows are free (or, beyond twice the fair share, by adding a
+    // channel group), so that one long CSR row cannot hold up its workgroup.
+    const int slots_per_group = h.WM * h.K;
+    std::vector<int> parts(d.M, h.WS);
+    long long n_vrows = (long long)d.M * h.WS;
+    long long n_groups = std::max<long long>(1, (n_vrows + slots_per_group - 1) / slots_per_group);
+    for (;;) {
+        const double fair = std::max(1.0, (double)nnz_total / ((double)n_groups * h.WM));
+        int worst = -1;
+        double worst_part = 0.0;
+        for (int m = 0; m < d.M; ++m) {
+            if (parts[m] >= h.WM) continue;
+            const double sz = (double)nnz_row[m] / parts[m];
+            if (sz > worst_part) { worst_part = sz; worst = m; }
+        }
+        if (worst < 0 || worst_part <= 1.25 * fair) break;
+        if (n_groups * slots_per_group - n_vrows <= 0) {
+            if (worst_part <= 2.0 * fair) break;
+            ++n_groups;
+            continue;
+        }
+        ++parts[worst];
+        ++n_vrows;
+    }
+    if (n_groups > (1 << 24)) return ESCOIN_ERANGE;
+    h.n_mgroups = (int)n_groups;
+    const int bins = h.n_mgroups * h.WM;
+
+    // Channels to groups, longest first, each to the group with the least work so far that
+    // still has room for all its parts.
+    std::vector<int> order(d.M);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return nnz_row[a] > nnz_row[b]; });
+    std::vector<std::vector<int>> group_rows(h.n_mgroups);
+    {
+        std::vector<long long> load(h.n_mgroups, 0);
+        std::vector<int> room(h.n_mgroups, slots_per_group);
+        for (int i = 0; i < d.M; ++i) {
+            const int m = order[i];
+            int best = -1, roomiest = 0;
+            for (int gi = 0; gi < h.n_mgroups; ++gi) {
+                if (room[gi] > room[roomiest]) roomiest = gi;
+                if (room[gi] >= parts[m] && (best < 0 || load[gi] < load[best])) best = gi;
+            }
+            if (best < 0) {  // fragmented free rows: fewer parts for this channel
+                best = roomiest;
+                parts[m] = room[best];
+                if (parts[m] < 1) return ESCOIN_ERANGE;  // cannot happen: rows were counted above
+            }
+            group_rows[best].push_back(m);
+            load[best] += nnz_row[m] + 1;
+            room[best] -= parts[m];
+        }
+    }
+
+    // Nonzeros of a (row, chunk, class) segment are dealt to the row's parts in turn, starting
+    // at a part that rotates with the segment so that no part collects all the remainders.
+    auto part_count = [&](int m, int ch, int cls, int part) {
+        const int n = rcc[((size_t)m * h.n_chunks + ch) * kClasses + cls], P = parts[m];
+        const int rot = (ch * kClasses + cls) % P;
+        const int first = ((part - rot) % P + P) % P;  // index of the part's first nonzero
+        return n / P + (first < n % P ? 1 : 0);
+    };
+
+    // Parts to waves.  The waves of a workgroup meet at a barrier after every chunk, so a
+    // workgroup's time is the sum over chunks of its slowest wave: the parts, longest first,
+    // each go to the wave (with a free accumulator row, and if possible without another part of
+    // the same channel) where they raise that sum the least.
+    std::vector<RowSlot> slot((size_t)bins * h.K);
+    for (auto& sl : slot) { sl.m = -1; sl.my_region = -1; sl.first_region = 0; sl.n_partials = 0; }
+    std::vector<int32_t> slot_part((size_t)bins * h.K, 0);
+    std::vector<int32_t> group_regions(h.n_mgroups, 0);
+    std::vector<int32_t> row_slot0(d.M, -1);        // index into row_slots of the row's part 0
+    std::vector<int32_t> row_slots;                 // slot index of every part, rows one after the other
+    row_slots.reserve((size_t)n_vrows);
+    int max_regions = 0;
+    {
+        struct Item { int m, part; long long total; };
+        std::vector<Item> items_v;
+        std::vector<int> batches, wave_load((size_t)h.WM * h.n_chunks), peak(h.n_chunks), wave_rows(h.WM);
+        std::vector<char> has_row;
         for (int mg = 0; mg < h.n_mgroups; ++mg) {
-            int32_t* pm = &perm[(size_t)mg * h.WM * h.K];
-            rows.clear();
-            for (int i = 0; i < h.WM * h.K; ++i)
-                if (pm[i] >= 0) rows.push_back(pm[i]);
-            std::vector<int> total(rows.size(), 0);
-            for (size_t i = 0; i < rows.size(); ++i)
+            items_v.clear();
+            for (int m : group_rows[mg])
+                for (int pt = 0; pt < parts[m]; ++pt) items_v.push_back({m, pt, 0});
+            batches.assign(items_v.size() * (size_t)h.n_chunks, 0);
+            for (size_t i = 0; i < items_v.size(); ++i)
                 for (int ch = 0; ch < h.n_chunks; ++ch) {
                     int nb = 0;
                     for (int cls = 0; cls < kClasses; ++cls)
-                        nb += ceil_div(rcc[((size_t)rows[i] * h.n_chunks + ch) * kClasses + cls], B);
+                        nb += ceil_div(part_count(items_v[i].m, ch, cls, items_v[i].part), B);
                     batches[i * h.n_chunks + ch] = nb;
-                    total[i] += nb;
+                    items_v[i].total += nb;
                 }
-            std::vector<int> idx(rows.size());
+            std::vector<int> idx(items_v.size());
             std::iota(idx.begin(), idx.end(), 0);
-            std::stable_sort(idx.begin(), idx.end(), [&](int a, int b) { return total[a] > total[b]; });
+            std::stable_sort(idx.begin(), idx.end(), [&](int a, int b) { return items_v[a].total > items_v[b].total; });
             std::fill(wave_load.begin(), wave_load.end(), 0);
             std::fill(peak.begin(), peak.end(), 0);
             std::fill(wave_rows.begin(), wave_rows.end(), 0);
-            std::fill(pm, pm + (size_t)h.WM * h.K, -1);
+            has_row.assign((size_t)h.WM * group_rows[mg].size(), 0);
+            // local index of a row inside this group
+            std::vector<std::pair<int, int>> loc;  // (m, local)
+            for (size_t i = 0; i < group_rows[mg].size(); ++i) loc.push_back({group_rows[mg][i], (int)i});
+            std::sort(loc.begin(), loc.end());
+            auto local_of = [&](int m) {
+                return std::lower_bound(loc.begin(), loc.end(), std::make_pair(m, 0))->second;
+            };
+            std::vector<int> placed_wave(items_v.size(), -1), placed_k(items_v.size(), -1);
             for (int i : idx) {
+                const int lm = local_of(items_v[i].m);
                 int best = -1;
                 long long best_rise = 0, best_total = 0;
+                bool best_sibling = true;
                 for (int w = 0; w < h.WM; ++w) {
                     if (wave_rows[w] >= h.K) continue;
+                    const bool sibling = has_row[(size_t)w * group_rows[mg].size() + lm] != 0;
                     long long rise = 0, tot = 0;
                     for (int ch = 0; ch < h.n_chunks; ++ch) {
                         const int v = wave_load[(size_t)w * h.n_chunks + ch] + batches[(size_t)i * h.n_chunks + ch];
                         rise += std::max(0, v - peak[ch]);
                         tot += wave_load[(size_t)w * h.n_chunks + ch];
                     }
-                    if (best < 0 || rise < best_rise || (rise == best_rise && tot < best_total)) {
-                        best = w; best_rise = rise; best_total = tot;
-                    }
+                    const bool better = best < 0 || (sibling != best_sibling ? !sibling
+                                                     : (rise != best_rise ? rise < best_rise : tot < best_total));
+                    if (better) { best = w; best_rise = rise; best_total = tot; best_sibling = sibling; }
                 }
+                if (best < 0) return ESCOIN_ERANGE;  // cannot happen: the group has room for its parts
                 for (int ch = 0; ch < h.n_chunks; ++ch) {
                     int& v = wave_load[(size_t)best * h.n_chunks + ch];
                     v += batches[(size_t)i * h.n_chunks + ch];
                     peak[ch] = std::max(peak[ch], v);
                 }
-                pm[(size_t)best * h.K + wave_rows[best]++] = rows[i];
+                has_row[(size_t)best * group_rows[mg].size() + lm] = 1;
+                placed_wave[i] = best;
+                placed_k[i] = wave_rows[best]++;
             }
+            // slots and LDS regions: part 0 owns the channel, the other parts lend partial sums
+            int regions = 0;
+            size_t i = 0;
+            for (int m : group_rows[mg]) {
+                row_slot0[m] = (int32_t)row_slots.size();
+                for (int pt = 0; pt < parts[m]; ++pt, ++i) {
+                    const size_t si = ((size_t)mg * h.WM + placed_wave[i]) * h.K + placed_k[i];
+                    slot[si].m = m;
+                    slot_part[si] = pt;
+                    if (pt == 0) {
+                        slot[si].first_region = regions;
+                        slot[si].n_partials = parts[m] - 1;
+                    } else {
+                        slot[si].my_region = regions++;
+                    }
+                    row_slots.push_back((int32_t)si);
+                }
+            }
+            group_regions[mg] = regions;
+            max_regions = std::max(max_regions, regions);
         }
     }
+    h.max_regions = max_regions;
 
     // ---- staging items per tile: every input word the window needs and where it lives in LDS
     struct WindowWord {
@@ -459,7 +570,7 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     // may then span two channels.
     bool flat_runs = false;
     if (h.VW == 1 && tiled_wide_staging_exists(h.K, h.Q, h.B) && h.n_tiles == 1 && d.C % 4 == 0 &&
-        h.CC % 4 == 0 && (int)items[0].size() == d.H * d.W) {
+        h.CC % 4 == 0 && h.CC0 % 4 == 0 && (int)items[0].size() == d.H * d.W) {
         flat_runs = true;
         for (size_t i = 0; i < items[0].size(); ++i) flat_runs = flat_runs && items[0][i].src == (int)i;
         if (flat_runs) h.VW = 4;
@@ -510,10 +621,10 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
                 uint32_t* sg = &seg[((size_t)bin * h.n_chunks + ch) * seg_stride];
                 sg[0] = (uint32_t)(total_batches - block_start);
                 for (int k = 0; k < h.K; ++k) {
-                    const int m = perm[(size_t)bin * h.K + k];
+                    const size_t si = (size_t)bin * h.K + k;
+                    const int m = slot[si].m;
                     for (int cls = 0; cls < kClasses; ++cls) {
-                        const int nb =
-                            m < 0 ? 0 : ceil_div(rcc[((size_t)m * h.n_chunks + ch) * kClasses + cls], B);
+                        const int nb = m < 0 ? 0 : ceil_div(part_count(m, ch, cls, slot_part[si]), B);
                         sg[1 + k * kClasses + cls] = (uint32_t)nb;
                         total_batches += nb;
                     }
@@ -531,7 +642,11 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     // wave's last one
     const uint64_t rec_buf = align_up64(max_block * B * 8 + (uint64_t)B * 8 + 16, 64);
     h.rec_buf_bytes = (int32_t)rec_buf;
-    const uint64_t lds_bytes = ((uint64_t)2 * h.buf_floats + h.tail_floats) * 4 + 2 * rec_buf;
+    // after the last chunk the same LDS holds the partial sums of split channels: one region
+    // per lending accumulator row, 16 bytes per lane and position run of every position wave
+    const uint64_t region_bytes = (uint64_t)h.WQ * h.Q * 64 * 16;
+    const uint64_t lds_bytes = std::max(((uint64_t)2 * h.buf_floats + h.tail_floats) * 4 + 2 * rec_buf,
+                                        (uint64_t)h.max_regions * region_bytes);
     if (lds_bytes > (uint64_t)kLdsBudgetBytes) return ESCOIN_ERANGE;
     h.lds_bytes = (int32_t)lds_bytes;
 
@@ -544,7 +659,7 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     h.off_dst_lut = off;
     off = align_up64(off + (uint64_t)h.n_tiles * h.P4 * 4, 256);
     h.off_perm = off;
-    off = align_up64(off + (uint64_t)perm.size() * 4, 256);
+    off = align_up64(off + (uint64_t)slot.size() * sizeof(RowSlot) + (uint64_t)h.n_mgroups * 4, 256);
     h.off_blk = off;
     off = align_up64(off + (uint64_t)blk.size() * 4, 256);
     h.off_seg = off;
@@ -597,7 +712,7 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
                         // channel cl's plane set, then image nl's columns inside the wide rows
                         const long long word =
                             items[t][i].dst + (long long)cl * h.NB * h.plane_stride + nl * h.pitch1;
-                        sl.key = (uint32_t)(word * 4) | ((uint32_t)cl << 24);
+                        sl.key = (uint32_t)(word * 4) | ((uint32_t)cl << kKeyOffsetBits);
                     }
                 }
                 slots[((size_t)t * kMaxItemsPerThread + j) * threads + tid] = sl;
@@ -622,38 +737,47 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     h.WW = wide_commit ? 4 : 1;
     std::memcpy(base, &h, sizeof(h));  // the header once more, now with WW
     std::memcpy(base + h.off_lanes, lanes.data(), lanes.size() * sizeof(LaneSlot));
-    std::memcpy(base + h.off_perm, perm.data(), perm.size() * 4);
+    std::memcpy(base + h.off_perm, slot.data(), slot.size() * sizeof(RowSlot));
+    std::memcpy(base + h.off_perm + slot.size() * sizeof(RowSlot), group_regions.data(), (size_t)h.n_mgroups * 4);
     std::memcpy(base + h.off_blk, blk.data(), blk.size() * 4);
     std::memcpy(base + h.off_seg, seg.data(), seg.size() * 4);
 
-    // ---- records: per (group, chunk, wave, row, class) in CSR order, padded to whole batches
-    // with (offset of the first group, value 0.0f): a padding record reads valid LDS and adds 0
+    // ---- records: per (group, chunk, wave, accumulator row, class) in CSR order, padded to whole
+    // batches with (the stretch of zeros behind the channel planes, value 0.0f)
     RowNz* rec = (RowNz*)(base + h.off_rec);
+    const uint32_t pad_off = (uint32_t)(((uint64_t)h.buf_floats - h.zero_floats) * 4 + 16);
     for (uint64_t i = 0; i < n_records; ++i) {
-        rec[i].off_bytes = 16;
+        rec[i].off_bytes = pad_off;
         rec[i].val = 0.0f;
     }
-    for (int bin = 0; bin < bins; ++bin) {
-        const int mg = bin / h.WM;
-        for (int k = 0; k < h.K; ++k) {
-            const int m = perm[(size_t)bin * h.K + k];
-            if (m < 0) continue;
-            std::vector<uint64_t> cursor((size_t)h.n_chunks * kClasses);
+    std::vector<uint64_t> cursor;
+    std::vector<int> seen((size_t)h.n_chunks * kClasses);
+    for (int m = 0; m < d.M; ++m) {
+        const int P = parts[m];
+        // where each part's records of every (chunk, class) segment start
+        cursor.assign((size_t)P * h.n_chunks * kClasses, 0);
+        for (int pt = 0; pt < P; ++pt) {
+            const size_t si = (size_t)row_slots[(size_t)row_slot0[m] + pt];
+            const int bin = (int)(si / h.K), k = (int)(si % h.K), mg = bin / h.WM;
             for (int ch = 0; ch < h.n_chunks; ++ch) {
                 const uint32_t* sg = &seg[((size_t)bin * h.n_chunks + ch) * seg_stride];
                 uint64_t at = (uint64_t)blk[((size_t)mg * h.n_chunks + ch) * 2] + sg[0];
                 for (int kk = 0; kk < k * kClasses; ++kk) at += sg[1 + kk];
                 for (int cls = 0; cls < kClasses; ++cls) {
-                    cursor[(size_t)ch * kClasses + cls] = at * B;
+                    cursor[((size_t)pt * h.n_chunks + ch) * kClasses + cls] = at * B;
                     at += sg[1 + k * kClasses + cls];
                 }
             }
-            for (int j = rowptr[m]; j < rowptr[m + 1]; ++j) {
-                uint64_t& at = cursor[(size_t)nz_chunk[j] * kClasses + nz_class[j]];
-                rec[at].off_bytes = nz_off[j];
-                rec[at].val = value[j];
-                ++at;
-            }
+        }
+        std::fill(seen.begin(), seen.end(), 0);
+        for (int j = rowptr[m]; j < rowptr[m + 1]; ++j) {
+            if (nz_chunk[j] < 0) continue;
+            const size_t sc = (size_t)nz_chunk[j] * kClasses + nz_class[j];
+            const int pt = (seen[sc]++ + (int)(sc % P)) % P;
+            uint64_t& at = cursor[(size_t)pt * h.n_chunks * kClasses + sc];
+            rec[at].off_bytes = nz_off[j];
+            rec[at].val = value[j];
+            ++at;
         }
     }
     return ESCOIN_OK;
@@ -677,7 +801,7 @@ int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_
     if (nnz > 0 && (!stretched || (out && !value))) return ESCOIN_EINVAL;
     if (tuning) {
         const int32_t* f = &tuning->K;
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < 10; ++i)
             if (f[i] < 0) return ESCOIN_EINVAL;
     }
 

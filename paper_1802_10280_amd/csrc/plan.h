@@ -11,7 +11,7 @@
 namespace escoin {
 
 constexpr uint32_t kPlanMagic = 0x4E4C5045u;  // "EPLN"
-constexpr uint32_t kPlanVersion = 12;
+constexpr uint32_t kPlanVersion = 13;
 constexpr int kMaxPhases = 16;          // stride*stride phase planes
 constexpr int kClasses = 4;             // alignment classes of a tap: (LDS offset) mod 4
 constexpr int kMaxItemsPerThread = 12;  // staged input words per thread and chunk
@@ -21,15 +21,27 @@ struct StageSlot {
     int32_t src;   // offset from the first input word of the chunk's first channel of the
                    // workgroup's first image: (image*C + channel)*H*W + offset in the plane;
                    // -1 = this thread has nothing to do in this slot
-    uint32_t key;  // bits 0..23: LDS byte offset of the word inside a window buffer;
-                   // bits 24..31: channel inside the chunk
+    uint32_t key;  // bits 0..17: LDS byte offset of the word inside a window buffer;
+                   // bits 18..31: channel inside the chunk
 };
+constexpr int kKeyOffsetBits = 18;                   // a window buffer is below 256 KB
+constexpr int kMaxChunkChannels = 1 << (32 - kKeyOffsetBits);
 
 // What one lane of a position run does: the 16-byte group it reads and the outputs it owns.
 struct LaneSlot {
     int32_t base_word;  // word index of the group inside a (channel 0) plane set
     int32_t pos0;       // first of its 4 positions inside the tile (index into dst_lut), -1 = nothing to store
     int32_t nloc;       // which of the tile's NB images those positions belong to
+};
+
+// One accumulator row of a wave: the output channel it works for and, when the channel's
+// nonzeros are split over several accumulator rows (of different waves of the workgroup), how
+// the partial sums meet in LDS after the last chunk.
+struct RowSlot {
+    int32_t m;             // output channel, -1 = unused accumulator row
+    int32_t my_region;     // >= 0: this row holds a partial sum and writes it to that LDS region
+    int32_t first_region;  // owner of a split channel: its partial sums sit in the regions
+    int32_t n_partials;    //   first_region .. first_region + n_partials - 1; 0 = nothing to add
 };
 
 struct PlanHeader {
@@ -40,9 +52,9 @@ struct PlanHeader {
     int32_t K;   // output channels (CSR rows) accumulated per wave
     int32_t Q;   // position runs (one 16-byte group per lane each) per wave
     int32_t B;   // nonzero records per batch
-    int32_t WM;  // waves of a workgroup along the output-channel axis
+    int32_t WM;  // waves of a workgroup along the output-channel axis (each has K accumulator rows)
     int32_t WQ;  // waves of a workgroup along the position axis
-    int32_t CC;  // input channels staged in LDS per chunk
+    int32_t CC;  // input channels staged in LDS per chunk (the first chunk holds CC0 <= CC)
     int32_t NB;  // images per workgroup
     int32_t TH;  // output rows per tile (band height)
     int32_t n_tiles, n_mgroups, n_chunks, n_phases;
@@ -52,7 +64,8 @@ struct PlanHeader {
     int32_t plane_stride;  // floats per (phase, channel) plane set in LDS divided by NB (multiple of 4)
     int32_t P4;            // positions of a tile (all its images) on the pitch grid (multiple of 4)
     int32_t n_items;       // input words per (tile, channel, image): the longest tile's count
-    int32_t buf_floats;    // floats of one LDS window buffer (two are allocated)
+    int32_t buf_floats;    // floats of one LDS window buffer (two are allocated): the channel
+                           // planes of a chunk followed by zero_floats floats nothing ever writes
     int32_t tail_floats;   // zeroed floats after the second window buffer
     int32_t rec_buf_bytes; // bytes of one LDS record buffer (two are allocated)
     int32_t lds_bytes;     // dynamic LDS size
@@ -61,7 +74,7 @@ struct PlanHeader {
     uint64_t off_items;    // StageSlot [n_tiles][kMaxItemsPerThread][threads of a workgroup]
     uint64_t off_lanes;    // LaneSlot [WQ*Q][64]
     uint64_t off_dst_lut;  // int32 [n_tiles][P4]: offset in an E*F plane, or -1
-    uint64_t off_perm;     // int32 [n_mgroups*WM][K]: output channel of each accumulator row, or -1
+    uint64_t off_perm;     // RowSlot [n_mgroups*WM][K], then int32 [n_mgroups]: LDS regions of the group
     uint64_t off_blk;      // uint32 [n_mgroups][n_chunks][2]: first batch, batches of the group's block
     uint64_t off_seg;      // uint32 [n_mgroups*WM][n_chunks][1+K*kClasses]: first batch inside the
                            // block, then batches per (row, class)
@@ -73,7 +86,11 @@ struct PlanHeader {
                      // words whose first is VW-word aligned inside the input tensor
     int32_t WW;      // 4: every run of VW = 4 words also lands on 4 consecutive, 16-byte aligned LDS
                      // words, so one 16-byte LDS write commits it; else 1
-    uint32_t reserved[4];
+    int32_t WS;          // least number of accumulator rows every output channel is split over
+    int32_t CC0;         // channels of the first chunk (a short one lets the first FMAs start early)
+    int32_t zero_floats; // floats at the end of every window buffer that stay zero: padding records
+                         // point there, so they multiply zeros whatever the input holds
+    int32_t max_regions; // most LDS regions (of WQ*Q*1024 bytes) a workgroup needs for partial sums
 };
 
 }  // namespace escoin

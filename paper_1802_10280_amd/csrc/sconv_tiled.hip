@@ -22,6 +22,8 @@
 // Consecutive lanes own consecutive positions (the data-to-thread mapping of Section 3.2), so
 // LDS reads are conflict-free and output stores are contiguous along w.
 #include <algorithm>
+#include <mutex>
+#include <vector>
 
 #include "common.h"
 #include "plan.h"
@@ -38,14 +40,15 @@ struct TiledArgs {
     const StageSlot* stage;
     const LaneSlot* lanes;
     const int32_t* dst_lut;
-    const int32_t* perm;
+    const RowSlot* slots;
+    const int32_t* group_regions;
     const uint32_t* blk;
     const uint32_t* seg;
     const uint32_t* rec;
     int N, C, HW, M, EF;
-    int WM, WQ, CC, NB, CS, WW;
+    int WM, WQ, CC, CC0, NB, CS, WW;
     int n_tiles, n_mgroups, n_chunks, n_in_tiles;
-    int plane_stride, P4, n_items, buf_floats, tail_floats, rec_buf_bytes;
+    int plane_stride, P4, n_items, buf_floats, tail_floats, rec_buf_bytes, region_floats;
     uint32_t flags;
 };
 
@@ -88,6 +91,8 @@ __device__ __forceinline__ void set_prio(int p) {
         default: __builtin_amdgcn_s_setprio(3); break;
     }
 }
+
+constexpr uint32_t kKeyOffsetMask = (1u << kKeyOffsetBits) - 1;
 
 template <int B>
 struct Batch {
@@ -153,7 +158,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     // ---- this thread's share of the staging work (the same for every chunk), from the plan
     constexpr int kRuns = kMaxItemsPerThread / VW;
     int st_src[kRuns];  // per run of VW words: offset from the chunk's first input word, -1 = none
-    // bits 0..23: LDS byte offset of the word inside a window buffer; 24..31: channel in the chunk
+    // bits 0..17: LDS byte offset of the word inside a window buffer; 18..31: channel in the chunk
     uint32_t st_key[kMaxItemsPerThread];
     {
         const StageSlot* __restrict__ sl = a.stage + (size_t)tile * kMaxItemsPerThread * nthreads + tid;
@@ -169,21 +174,23 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     const int win_bytes = a.buf_floats * 4;
     const int rec_base = (2 * a.buf_floats + a.tail_floats) * 4;  // first record buffer
     cu32p blkp = as_const(a.blk) + (size_t)mg * a.n_chunks * 2;
-    const int bin = mg * a.WM + wm;
     constexpr int kSeg = 1 + K * kClasses;
-    cu32p segp = as_const(a.seg) + (size_t)bin * a.n_chunks * kSeg;
+    cu32p segp = as_const(a.seg) + ((size_t)mg * a.WM + wm) * a.n_chunks * kSeg;
 
     float st_val[kMaxItemsPerThread];
 
     // Issue the global loads of chunk `ch`: window words into registers, the record block
     // straight into record buffer `buf` (global_load ... lds, 16 bytes per lane, no registers).
+    // chunk `ch` holds the channels c0 .. c0 + ccur - 1: the first chunk CC0 of them, the others CC
+    auto chunk_c0 = [&](int ch) { return ch == 0 ? 0 : a.CC0 + (ch - 1) * a.CC; };
+    auto chunk_len = [&](int ch) { return ch == 0 ? a.CC0 : min(a.CC, a.C - chunk_c0(ch)); };
     auto fetch = [&](int ch, int buf) {
-        const int c0 = ch * a.CC;
-        const int ccur = min(a.CC, a.C - c0);
+        const int c0 = chunk_c0(ch);
+        const int ccur = chunk_len(ch);
         const float* __restrict__ src = a.in + ((size_t)n0 * a.C + c0) * a.HW;
 #pragma unroll
         for (int r = 0; r < kRuns; ++r)
-            if (st_src[r] >= 0 && (int)(st_key[r * VW] >> 24) < ccur) {
+            if (st_src[r] >= 0 && (int)(st_key[r * VW] >> kKeyOffsetBits) < ccur) {
                 if (VW == 4) {
                     const f4 v = *(const f4*)__builtin_assume_aligned(src + st_src[r], 16);
                     st_val[4 * r] = v[0]; st_val[4 * r + 1] = v[1]; st_val[4 * r + 2] = v[2]; st_val[4 * r + 3] = v[3];
@@ -202,22 +209,22 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     };
     // Write the window words fetch(ch) loaded into window buffer `buf`.
     auto commit = [&](int ch, int buf) {
-        const int ccur = min(a.CC, a.C - ch * a.CC);
+        const int ccur = chunk_len(ch);
         char* const win = lds_bytes + buf * win_bytes;
         if (VW == 4 && a.WW == 4) {  // every run lands on 16 aligned, consecutive LDS bytes
 #pragma unroll
             for (int r = 0; r < kRuns; ++r)
-                if (st_src[r] >= 0 && (int)(st_key[4 * r] >> 24) < ccur) {
+                if (st_src[r] >= 0 && (int)(st_key[4 * r] >> kKeyOffsetBits) < ccur) {
                     f4 v;
                     v[0] = st_val[4 * r]; v[1] = st_val[4 * r + 1]; v[2] = st_val[4 * r + 2]; v[3] = st_val[4 * r + 3];
-                    *(f4*)__builtin_assume_aligned(win + (st_key[4 * r] & 0xFFFFFF), 16) = v;
+                    *(f4*)__builtin_assume_aligned(win + (st_key[4 * r] & kKeyOffsetMask), 16) = v;
                 }
             return;
         }
 #pragma unroll
         for (int j = 0; j < kMaxItemsPerThread; ++j)
-            if (st_src[j / VW] >= 0 && (int)(st_key[j] >> 24) < ccur)
-                *(float*)(win + (st_key[j] & 0xFFFFFF)) = st_val[j];
+            if (st_src[j / VW] >= 0 && (int)(st_key[j] >> kKeyOffsetBits) < ccur)
+                *(float*)(win + (st_key[j] & kKeyOffsetMask)) = st_val[j];
     };
 
     // This workgroup's chunks: cs, cs + CS, ... (all of them unless the channels are split).
@@ -237,12 +244,77 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
 #pragma unroll
         for (int q = 0; q < Q; ++q) acc[k][q] = (f4)(0.0f);
 
-    for (int ch = cs, it = 0; ch < a.n_chunks; ch += a.CS, ++it) {
-        const int buf = it & 1;
-        const bool more = ch + a.CS < a.n_chunks;
-        if (more) fetch(ch + a.CS, buf ^ 1);
+    // The wave's K accumulator rows: output channel, and how a channel whose nonzeros are
+    // split over several accumulator rows of the workgroup is put together after the last chunk.
+    const int bin = mg * a.WM + wm;
+    RowSlot rs[K];
+    {
+        ci32p sp = as_const((const int32_t*)a.slots) + (size_t)bin * K * 4;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            rs[k].m = sp[4 * k];
+            rs[k].my_region = sp[4 * k + 1];
+            rs[k].first_region = sp[4 * k + 2];
+            rs[k].n_partials = sp[4 * k + 3];
+        }
+    }
+    // With split channels every workgroup adds its partial sums to an output that was cleared
+    // before the launch; the first split brings the bias and the clamp is a pass of its own.
+    const bool split = a.CS > 1;
+    const int32_t* __restrict__ dlut = a.dst_lut + (size_t)tile * a.P4;
+    // Where this lane's positions go inside an E*F output plane (-1: not an output).  The
+    // offsets are fetched at the start of the last chunk, when the staging registers are free
+    // (nothing is fetched any more), and live there until the stores.
+    auto load_dst = [&]() {
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int dd = -1;
+                if (pos0[q] >= 0 && n0 + nloc[q] < a.N) dd = dlut[pos0[q] + i];
+                st_val[q * 4 + i] = __int_as_float(dd);
+            }
+    };
+    static_assert(Q * 4 <= kMaxItemsPerThread, "the output offsets borrow the staging registers");
+    // Row k of this wave is complete: epilogue and store (or atomic add with split channels).
+    auto store_row = [&](int k, const f4(&ak)[Q]) {
+        const int m = rs[k].m;
+        const float bv = ((a.flags & ESCOIN_F_BIAS) && cs == 0) ? a.bias[m] : 0.0f;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            int dofs[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dofs[i] = __float_as_int(st_val[q * 4 + i]);
+            float* __restrict__ o = a.out + ((size_t)(n0 + nloc[q]) * a.M + m) * a.EF;
+            f4 v = ak[q] + bv;
+            if (split) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (dofs[i] >= 0) unsafeAtomicAdd(o + dofs[i], v[i]);
+                continue;
+            }
+            if (a.flags & ESCOIN_F_RELU) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = v[i] > 0.0f ? v[i] : 0.0f;
+            }
+            // A lane whose four positions are four consecutive, 16-byte aligned output words
+            // stores them at once.
+            const bool quad = (a.EF & 3) == 0 && ((uintptr_t)a.out & 15) == 0 && dofs[0] >= 0 && (dofs[0] & 3) == 0 &&
+                              dofs[1] == dofs[0] + 1 && dofs[2] == dofs[0] + 2 && dofs[3] == dofs[0] + 3;
+            if (quad) {
+                *(f4*)__builtin_assume_aligned(o + dofs[0], 16) = v;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (dofs[i] >= 0) o[dofs[i]] = v[i];
+            }
+        }
+    };
 
-        // ---- compute: Algorithm 2 over this chunk's nonzeros of the wave's K rows
+    // Algorithm 2 over chunk `ch`'s nonzeros of the wave's K rows, on window buffer `buf`.
+    // LAST: the workgroup's last chunk, after which a row that is whole in this wave is stored.
+    auto compute = [&](int ch, int buf, auto last_tag) {
+        constexpr bool LAST = decltype(last_tag)::value;
         const int bufb = buf * win_bytes;
         cu32p sg = segp + (size_t)ch * kSeg;
         // all segment lengths of the chunk in one scalar load, not one load per segment
@@ -297,64 +369,52 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
             run_class(std::integral_constant<int, 2>{}, acc[k], (int)cnts[1 + k * kClasses + 2]);
             set_prio(3 - (k * kClasses + 3) / K);
             run_class(std::integral_constant<int, 3>{}, acc[k], (int)cnts[1 + k * kClasses + 3]);
+            // The stores of rows 0 .. K-2 run under the arithmetic of the rows after them
+            // instead of all workgroups storing at once at the end of the launch.
+            if (LAST && rs[k].m >= 0 && rs[k].my_region < 0 && rs[k].n_partials == 0) store_row(k, acc[k]);
         }
         set_prio(3);
+    };
+
+    int ch = cs, it = 0;
+    for (; ch + a.CS < a.n_chunks; ch += a.CS, ++it) {
+        const int buf = it & 1;
+        fetch(ch + a.CS, buf ^ 1);
+        compute(ch, buf, std::false_type{});
         // The other buffers were last read in the previous iteration, which every wave left
         // through the barrier below: they can be rewritten now.
-        if (more) commit(ch + a.CS, buf ^ 1);
+        commit(ch + a.CS, buf ^ 1);
         __builtin_amdgcn_s_waitcnt(0);  // this wave's record copies have landed
         __syncthreads();
     }
+    // the last chunk: nothing to fetch any more, so the staging registers take the output offsets
+    load_dst();
+    compute(ch, it & 1, std::true_type{});
 
-    // ---- store
-    const int32_t* __restrict__ dlut = a.dst_lut + (size_t)tile * a.P4;
-    int dofs[Q][4];
+    // ---- channels split over several accumulator rows: the lending rows put their partial
+    // sums into LDS (the window is no longer needed once every wave has left the last chunk),
+    // the owning row adds them up and stores.
+    if (as_const(a.group_regions)[mg] > 0) {
+        __syncthreads();  // every wave is done with the window and the records
+        const int mine = ((wq * Q) * 64 + lane) * 4;  // floats; run q sits q * 256 floats further
 #pragma unroll
-    for (int q = 0; q < Q; ++q)
+        for (int k = 0; k < K; ++k)
+            if (rs[k].my_region >= 0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int d = -1;
-            if (pos0[q] >= 0 && n0 + nloc[q] < a.N) d = dlut[pos0[q] + i];
-            dofs[q][i] = d;
-        }
-    // A lane whose four positions are four consecutive, 16-byte aligned output words stores
-    // them at once.
-    bool quad[Q];
-#pragma unroll
-    for (int q = 0; q < Q; ++q)
-        quad[q] = (a.EF & 3) == 0 && ((uintptr_t)a.out & 15) == 0 && dofs[q][0] >= 0 && (dofs[q][0] & 3) == 0 && dofs[q][1] == dofs[q][0] + 1 &&
-                  dofs[q][2] == dofs[q][0] + 2 && dofs[q][3] == dofs[q][0] + 3;
-    // With split channels every workgroup adds its partial sums to an output that was cleared
-    // before the launch; the first split brings the bias and the clamp is a pass of its own.
-    const bool split = a.CS > 1;
-    ci32p pm = as_const(a.perm) + (size_t)bin * K;
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const int m = pm[k];
-        if (m < 0) continue;  // uniform: padding row of the last group
-        const float bv = ((a.flags & ESCOIN_F_BIAS) && cs == 0) ? a.bias[m] : 0.0f;
-#pragma unroll
-        for (int q = 0; q < Q; ++q) {
-            float* __restrict__ o = a.out + ((size_t)(n0 + nloc[q]) * a.M + m) * a.EF;
-            f4 v = acc[k][q] + bv;
-            if (split) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (dofs[q][i] >= 0) unsafeAtomicAdd(o + dofs[q][i], v[i]);
-                continue;
+                for (int q = 0; q < Q; ++q)
+                    *(f4*)__builtin_assume_aligned(&lds[(size_t)rs[k].my_region * a.region_floats + mine + q * 256], 16) = acc[k][q];
             }
-            if (a.flags & ESCOIN_F_RELU) {
+        __syncthreads();
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = v[i] > 0.0f ? v[i] : 0.0f;
-            }
-            if (quad[q]) {
-                *(f4*)__builtin_assume_aligned(o + dofs[q][0], 16) = v;
-            } else {
+        for (int k = 0; k < K; ++k)
+            if (rs[k].m >= 0 && rs[k].n_partials > 0) {
+                for (int i = 0; i < rs[k].n_partials; ++i)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (dofs[q][i] >= 0) o[dofs[q][i]] = v[i];
+                    for (int q = 0; q < Q; ++q)
+                        acc[k][q] += *(const f4*)__builtin_assume_aligned(
+                            &lds[(size_t)(rs[k].first_region + i) * a.region_floats + mine + q * 256], 16);
+                store_row(k, acc[k]);
             }
-        }
     }
 }
 
@@ -370,6 +430,27 @@ __global__ __launch_bounds__(256) void relu_kernel(float* __restrict__ p, size_t
 }
 
 typedef void (*TiledKernel)(const TiledArgs);
+
+// A kernel that wants more than 64 KB of dynamic LDS has to be told so once per device; the
+// largest size granted so far is remembered, so that later launches skip the runtime call.
+int allow_dynamic_lds(const void* kernel, int bytes) {
+    struct Granted { int device; const void* kernel; int bytes; };
+    static std::mutex mu;
+    static std::vector<Granted> granted;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return ESCOIN_EHIP;
+    std::lock_guard<std::mutex> lock(mu);
+    for (Granted& gr : granted)
+        if (gr.device == dev && gr.kernel == kernel) {
+            if (gr.bytes >= bytes) return ESCOIN_OK;
+            if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return ESCOIN_EHIP;
+            gr.bytes = bytes;
+            return ESCOIN_OK;
+        }
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return ESCOIN_EHIP;
+    granted.push_back({dev, kernel, bytes});
+    return ESCOIN_OK;
+}
 
 // (K, Q, B) instantiations: the ones that fit 128 VGPRs (four waves per SIMD) without spilling.
 #define ESCOIN_TILED_VARIANTS(X) \
@@ -435,13 +516,19 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     const int threads = 64 * h.WQ * h.WM;
     if (threads > 1024 || threads <= 0) return ESCOIN_EINVAL;
     // the kernel's index arithmetic relies on these plan invariants
+    const long long region_bytes = (long long)h.WQ * h.Q * 64 * 16;
     if (h.P4 % 4 || h.plane_stride % 4 || (long long)h.P4 > (long long)h.NB * h.plane_stride || h.NB < 1 || h.CC < 1 ||
-        h.WQ < 1 || h.WM < 1 || h.tail_floats % 4 || h.rec_buf_bytes % 16 || h.front < 4 ||
+        h.CC > kMaxChunkChannels || h.CC0 < 1 || h.CC0 > h.CC ||
+        h.n_chunks != (d.C <= h.CC0 ? 1 : 1 + (d.C - h.CC0 + h.CC - 1) / h.CC) ||
+        h.WQ < 1 || h.WM < 1 || h.WS < 1 || h.WS > h.WM || h.tail_floats % 4 || h.rec_buf_bytes % 16 || h.front < 4 ||
         h.n_phases < 1 || h.n_phases > kMaxPhases || (h.VW != 1 && h.VW != 4) || (h.WW != 1 && h.WW != 4) || (h.WW == 4 && h.VW != 4) || h.CS < 1 || h.CS > h.n_chunks ||
-        h.buf_floats != h.n_phases * h.CC * h.NB * h.plane_stride ||
+        h.zero_floats % 4 || h.zero_floats < h.P4 + 16 ||
+        (long long)h.buf_floats != (long long)h.n_phases * h.CC * h.NB * h.plane_stride + h.zero_floats ||
         (long long)h.n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads ||
-        (long long)h.buf_floats * 4 >= (1 << 24) ||
-        h.lds_bytes != (2 * h.buf_floats + h.tail_floats) * 4 + 2 * h.rec_buf_bytes)
+        (long long)h.buf_floats * 4 >= (1 << kKeyOffsetBits) || h.max_regions < 0 ||
+        h.lds_bytes != std::max((long long)(2 * h.buf_floats + h.tail_floats) * 4 + 2 * h.rec_buf_bytes,
+                                h.max_regions * region_bytes) ||
+        h.lds_bytes > 160 * 1024)
         return ESCOIN_EINVAL;
 
     const char* base = (const char*)d_plan;
@@ -450,12 +537,13 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     a.stage = (const StageSlot*)(base + h.off_items);
     a.lanes = (const LaneSlot*)(base + h.off_lanes);
     a.dst_lut = (const int32_t*)(base + h.off_dst_lut);
-    a.perm = (const int32_t*)(base + h.off_perm);
+    a.slots = (const RowSlot*)(base + h.off_perm);
+    a.group_regions = (const int32_t*)(base + h.off_perm + (size_t)h.n_mgroups * h.WM * h.K * sizeof(RowSlot));
     a.blk = (const uint32_t*)(base + h.off_blk);
     a.seg = (const uint32_t*)(base + h.off_seg);
     a.rec = (const uint32_t*)(base + h.off_rec);
     a.N = d.N; a.C = d.C; a.HW = d.H * d.W; a.M = d.M; a.EF = d.E * d.F;
-    a.WM = h.WM; a.WQ = h.WQ; a.CC = h.CC; a.NB = h.NB; a.CS = h.CS; a.WW = h.WW;
+    a.WM = h.WM; a.WQ = h.WQ; a.CC = h.CC; a.CC0 = h.CC0; a.NB = h.NB; a.CS = h.CS; a.WW = h.WW;
     a.n_tiles = h.n_tiles; a.n_mgroups = h.n_mgroups; a.n_chunks = h.n_chunks;
     const long long n_in_tiles = (long long)h.n_tiles * ((d.N + h.NB - 1) / h.NB);
     const long long blocks = (n_in_tiles * h.n_mgroups * h.CS + 7) / 8 * 8;
@@ -463,13 +551,13 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     a.n_in_tiles = (int)n_in_tiles;
     a.plane_stride = h.plane_stride; a.P4 = h.P4; a.n_items = h.n_items;
     a.buf_floats = h.buf_floats; a.tail_floats = h.tail_floats; a.rec_buf_bytes = h.rec_buf_bytes;
+    a.region_floats = h.WQ * h.Q * 256;
     a.flags = flags;
 
     const size_t lds_bytes = (size_t)h.lds_bytes;
     if (lds_bytes > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return ESCOIN_EHIP;
+        rc = allow_dynamic_lds((const void*)kern, (int)lds_bytes);
+        if (rc != ESCOIN_OK) return rc;
     }
     if (h.CS == 1)
         return launch(kern, dim3((unsigned)blocks), dim3(threads), lds_bytes, (hipStream_t)hip_stream, a);

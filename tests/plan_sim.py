@@ -32,14 +32,21 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
     K, Q, B, WM, WQ, CC, NB = h["K"], h["Q"], h["B"], h["WM"], h["WQ"], h["CC"], h["NB"]
     ps, P4 = h["plane_stride"], h["P4"]
     threads = 64 * WQ * WM
-    # staging slots: [tile][slot][thread] of (src offset, LDS byte | channel << 24)
+    # staging slots: [tile][slot][thread] of (src offset, LDS byte | channel << 18)
     slots = plan[h["off_items"]:h["off_items"] + 8 * h["n_tiles"] * 12 * threads].view(np.uint32)
     slots = slots.reshape(h["n_tiles"], 12 * threads, 2)
     runs = WQ * Q
     lanes = plan[h["off_lanes"]:h["off_lanes"] + 12 * runs * 64].view(np.int32).reshape(runs, 64, 3)
     dst = plan[h["off_dst_lut"]:h["off_dst_lut"] + 4 * h["n_tiles"] * P4].view(np.int32).reshape(h["n_tiles"], P4)
     bins = h["n_mgroups"] * WM
-    perm = plan[h["off_perm"]:h["off_perm"] + 4 * bins * K].view(np.int32).reshape(bins, K)
+    # accumulator rows: (output channel, region it lends a partial sum to, first region and
+    # count of the partial sums it collects), then the number of regions of every channel group
+    rows = plan[h["off_perm"]:h["off_perm"] + 16 * bins * K].view(np.int32).reshape(bins, K, 4)
+    group_regions = plan[h["off_perm"] + 16 * bins * K:h["off_perm"] + 16 * bins * K + 4 * h["n_mgroups"]].view(np.int32)
+    perm = rows[:, :, 0]
+    CC0, ZF = h["CC0"], h["zero_floats"]
+    assert 1 <= CC0 <= CC and h["n_chunks"] == (1 if C <= CC0 else 1 + -(-(C - CC0) // CC))
+    assert 1 <= h["WS"] <= WM
     sw = 1 + K * NCLS
     seg = plan[h["off_seg"]:h["off_seg"] + 4 * bins * h["n_chunks"] * sw].view(np.uint32)
     seg = seg.reshape(bins, h["n_chunks"], sw)
@@ -48,7 +55,16 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
     rec = plan[h["off_rec"]:h["off_rec"] + 8 * h["n_records"]]
     rec_off = rec.view(np.uint32)[0::2]
     rec_val = rec.view(np.float32)[1::2]
-    assert sorted(perm[perm >= 0].tolist()) == list(range(M)), "perm must cover every row once"
+    owners = rows[(rows[:, :, 0] >= 0) & (rows[:, :, 1] < 0)]
+    assert sorted(owners[:, 0].tolist()) == list(range(M)), "every output channel needs exactly one owning row"
+    for mgi in range(h["n_mgroups"]):
+        grp = rows[mgi * WM:(mgi + 1) * WM].reshape(-1, 4)
+        lend = grp[(grp[:, 0] >= 0) & (grp[:, 1] >= 0)]
+        assert sorted(lend[:, 1].tolist()) == list(range(group_regions[mgi])), "regions of a group: one lender each"
+        assert group_regions[mgi] <= h["max_regions"]
+        for m_, _, first, cnt in grp[(grp[:, 0] >= 0) & (grp[:, 1] < 0)]:
+            assert (lend[(lend[:, 1] >= first) & (lend[:, 1] < first + cnt), 0] == m_).all() and \
+                   (lend[:, 0] == m_).sum() == cnt, "an owner collects exactly its channel's partial sums"
     # every position of the (wide) tile is owned by exactly one lane
     assert h["pitch"] == NB * h["pitch1"] and h["pitch1"] >= 1
     owned = np.zeros(P4, dtype=int)
@@ -80,9 +96,12 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
     out = np.full((N, M, h["E"] * h["F"]), np.nan)
     xf = x.reshape(N, C, H * W).astype(np.float64)
     buf_floats = h["buf_floats"]
-    assert buf_floats == h["n_phases"] * CC * NB * ps
+    assert buf_floats == h["n_phases"] * CC * NB * ps + ZF and ZF >= P4 + 16
     lds_len = buf_floats + h["tail_floats"]            # one window buffer plus the zeroed tail
-    assert h["lds_bytes"] == (2 * buf_floats + h["tail_floats"]) * 4 + 2 * h["rec_buf_bytes"]
+    assert h["lds_bytes"] == max((2 * buf_floats + h["tail_floats"]) * 4 + 2 * h["rec_buf_bytes"],
+                                 h["max_regions"] * WQ * Q * 1024) <= 160 * 1024
+    assert buf_floats * 4 < (1 << 18)
+    pad_off = (buf_floats - ZF) * 4 + 16
     assert threads <= 1024 and h["n_items"] * CC * NB <= 12 * threads
     xflat = x.reshape(-1).astype(np.float64)
     for t in range(h["n_tiles"]):
@@ -90,17 +109,21 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
             nb = min(NB, N - n0)
             acc = np.zeros((bins, K, runs, 64, 4))
             for ch in range(h["n_chunks"]):
-                c0 = ch * CC
-                ccur = min(CC, C - c0)
+                c0 = 0 if ch == 0 else CC0 + (ch - 1) * CC
+                ccur = CC0 if ch == 0 else min(CC, C - c0)
+                assert ccur >= 1 and c0 + ccur <= C
                 # the frame was zeroed once; the staging items rewrite the words that hold input
                 lds = np.zeros(lds_len)
                 src = slots[t][:, 0].view(np.int32).astype(np.int64)
                 key = slots[t][:, 1]
                 # the kernel's tests: a slot in use, an image inside the batch, a channel inside C
-                live = (src >= 0) & (src < nb * C * H * W) & ((key >> 24) < ccur)
-                where = (key[live] & 0xFFFFFF).astype(np.int64)
+                live = (src >= 0) & (src < nb * C * H * W) & ((key >> 18) < ccur)
+                where = (key[live] & 0x3FFFF).astype(np.int64)
                 assert np.all(where % 4 == 0) and len(set(where.tolist())) == len(where)
-                lds[where // 4] = xflat[(n0 * C + c0) * H * W + src[live]]
+                assert where.max(initial=0) < (buf_floats - ZF) * 4, "staging must not touch the zero stretch"
+                gsrc = (n0 * C + c0) * H * W + src[live]
+                assert gsrc.max(initial=0) < N * C * H * W, "staging reads past the end of the input"
+                lds[where // 4] = xflat[gsrc]
                 for b in range(bins):
                     mgi = b // WM
                     assert seg[b, ch, 0] + seg[b, ch, 1:].sum() <= blk[mgi, ch, 1]
@@ -112,17 +135,31 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
                             for j in range(at, at + cnt):
                                 off = int(rec_off[j])
                                 assert off % 16 == 0
+                                if rec_val[j] == 0.0:      # only padding records carry a zero
+                                    assert off == pad_off
                                 o = off // 4
                                 for r in range(runs):
                                     idx = lanes[r, :, 0][:, None] + o + np.arange(4)[None, :]
                                     assert idx.min() >= 0 and idx.max() < lds_len
                                     acc[b, k, r] += float(rec_val[j]) * _window_words(lds[idx], cls)
                             at += cnt
+            # channels split over several accumulator rows: the owner adds the lenders' sums
+            for b in range(bins):
+                for k in range(K):
+                    m, mine, first, cnt = rows[b, k]
+                    if m < 0 or mine >= 0:
+                        continue
+                    g0 = (b // WM) * WM
+                    for bb in range(g0, g0 + WM):
+                        for kk in range(K):
+                            if rows[bb, kk, 0] == m and rows[bb, kk, 1] >= 0:
+                                assert first <= rows[bb, kk, 1] < first + cnt
+                                acc[b, k] += acc[bb, kk]
             d = dst[t]
             for b in range(bins):
                 for k in range(K):
                     m = perm[b, k]
-                    if m < 0:
+                    if m < 0 or rows[b, k, 1] >= 0:
                         continue
                     for r in range(runs):
                         for l in range(64):

@@ -95,6 +95,11 @@ TUNINGS = [
     dict(K=2, Q=2, B=2, WM=2, CC=1, CS=2, TH=7),
     dict(K=1, Q=1, B=2, WM=3, CC=4, NB=3),          # 16-byte staging runs across channels where C % 4 == 0
     dict(K=2, Q=2, B=2, WM=2, CC=8, NB=2),
+    dict(K=2, Q=1, B=2, WM=4, WS=2, CC=3, TH=5),            # every channel split over two waves, sums meet in LDS
+    dict(K=4, Q=2, B=2, WM=4, WS=4, CC=4, CC0=2, NB=2),     # four ways, short first chunk
+    dict(K=1, Q=2, B=2, WM=6, WS=3, CC=5, CC0=1),
+    dict(K=2, Q=2, B=2, WM=4, WS=2, CC=2, CS=2),            # split over waves and over workgroups
+    dict(K=8, Q=1, B=2, WM=2, WS=2, CC=3, CC0=1, TH=4),
 ]
 
 
@@ -108,19 +113,46 @@ def test_tiled_every_template_and_tiling(oracle, cfg, tune):
     N, C, H, W, M, R, S, stride, pad, sp = cfg
     L = wl.custom_layer(N, C, H, W, M, R, S, stride, pad, sp, seed=sum(cfg[:9]) + 2, dist="normal")
     t = dict(tune)
-    if "NB" in t and "TH" not in t:
-        pass
     flags = esc.F_BIAS | (esc.F_RELU if "CS" in t else 0)   # the split path clamps in a pass of its own
     try:
         dl = DeviceLayer(esc, L, tuning=t)
         got = dl.forward_tiled(flags)
     except esc.EscoinError as e:
-        assert e.code == esc.ERANGE       # a tiling that needs more than 8 waves or too much LDS
+        assert e.code == esc.ERANGE       # a tiling that needs more than 16 waves or too much LDS
         pytest.skip("tiling not realisable for this shape")
+    REALISED.add(TUNINGS.index(tune))
     ref, bound = oracle_full(oracle, L, flags)
     assert_within_bound(got, ref, bound, f"{cfg} {tune}")
     if "CS" in t:  # a second call must clear the first call's sums before adding to them
         assert_within_bound(dl.forward_tiled(flags), ref, bound, f"{cfg} {tune} again")
+
+
+REALISED = set()
+
+
+def test_every_tuning_was_realised_on_some_shape():
+    """Runs after the tuning sweep above: a tiling that no shape could realise would be untested."""
+    assert REALISED == set(range(len(TUNINGS))), sorted(set(range(len(TUNINGS))) - REALISED)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_non_finite_inputs_stay_where_the_definition_puts_them(oracle, path):
+    """An Inf or NaN in the input may only reach the outputs whose window holds it under a
+    nonzero weight: records that merely fill a batch, idle lanes and the zero frame must not
+    spread it."""
+    print("sconv non-finite input", path, flush=True)
+    L = wl.custom_layer(3, 7, 12, 13, 9, 3, 3, 1, 1, 0.7, seed=99, dist="normal")
+    L.input[1, 2, 5, 6] = np.inf
+    L.input[2, 0, 0, 0] = np.nan
+    L.input[0, 6, 11, 12] = -np.inf
+    for tune in (None, dict(K=2, Q=2, B=2, WM=4, WS=2, CC=3, CC0=1, NB=2)) if path == "tiled" else (None,):
+        got = DeviceLayer(esc, L, tuning=tune).run(path, 0)
+        with np.errstate(invalid="ignore", over="ignore"):
+            ref, bound = oracle_full(oracle, L, 0)
+        bad_ref = ~np.isfinite(ref)
+        assert bad_ref.any() and (bad_ref == ~np.isfinite(got)).all(), (path, tune, bad_ref.sum(), (~np.isfinite(got)).sum())
+        ok = ~bad_ref
+        assert (np.abs(got[ok] - ref[ok]) <= 1e-4 * bound[ok]).all()
 
 
 @pytest.mark.parametrize("path", PATHS)
@@ -277,6 +309,10 @@ def test_tiled_random_layers_and_tilings(oracle):
             tune["TH"] = int(rng.integers(1, L.spec.E + 1))
         if rng.random() < 0.3:
             tune["CS"] = int(rng.integers(1, 4))
+        if rng.random() < 0.4:
+            tune["WS"] = int(rng.integers(1, 5))
+        if rng.random() < 0.3:
+            tune["CC0"] = int(rng.integers(1, C + 1))
         flags = int(rng.integers(0, 4))
         print("sconv tiled random", it, (N, C, H, W, M, R, S, stride, pad), tune, flags, flush=True)
         try:

@@ -32,6 +32,14 @@ CASES = [
     ((5, 6, 11, 1, 10, 4, 1, 1, 3, 0.0), dict(CC=3, NB=3)),          # output rows wider than W + pad
     ((6, 8, 7, 7, 9, 3, 3, 1, 1, 0.6), dict(K=1, NB=4, CC=4)),       # 16-byte staging runs across channels
     ((3, 12, 13, 13, 7, 3, 3, 1, 1, 0.6), dict(K=2, Q=2, NB=2, CC=8)),  # the same with a shorter last chunk
+    ((2, 5, 9, 11, 7, 3, 3, 1, 1, 0.6), dict(K=2, WM=4, WS=2)),         # every channel split over two waves
+    ((3, 6, 7, 7, 10, 3, 3, 1, 1, 0.7), dict(K=4, NB=2, CC=4, WM=4, WS=4, CC0=2)),  # four ways, short first chunk
+    ((2, 6, 17, 19, 5, 3, 3, 2, 1, 0.6), dict(K=1, WM=3, WS=3, CC=4, CC0=1)),        # stride 2, three ways
+    ((4, 8, 7, 7, 6, 3, 3, 1, 1, 0.5), dict(K=2, Q=2, NB=4, WM=6, WS=3, CC=4, CC0=4, CS=2)),  # split waves and workgroups
+    # chunks of more than 256 channels: the staging key must keep the whole channel number
+    ((1, 1501, 2, 2, 2048, 1, 1, 1, 0, 0.99), {}),
+    ((2, 700, 2, 2, 8, 1, 1, 1, 0, 0.9), dict(CC=400, CS=1)),
+    ((30, 1500, 1, 1, 2048, 1, 1, 1, 0, 0.999), dict(NB=1)),
 ]
 
 
@@ -46,6 +54,8 @@ def test_plan_replay_matches_oracle(oracle, cfg, tune):
     assert h["total_bytes"] == plan.nbytes and h["nnz"] == L.nnz
     for k, v in tune.items():
         assert h[k] == v, (k, h[k], v)
+    if C > 256 and not tune.get("CC"):
+        assert h["CC"] > 256                     # the case the 8-bit channel field could not hold
     if cfg[:4] in ((6, 8, 7, 7), (3, 12, 13, 13)):
         assert h["VW"] == 4                      # the flat (channel, row, column) runs
     got = simulate(plan, L.input, M)
@@ -80,6 +90,10 @@ def test_random_layers_and_tilings_replay(oracle):
             tune["TH"] = int(rng.integers(1, L.spec.E + 1))
         if rng.random() < 0.3:
             tune["CS"] = int(rng.integers(1, 4))
+        if rng.random() < 0.4:
+            tune["WS"] = int(rng.integers(1, 5))
+        if rng.random() < 0.3:
+            tune["CC0"] = int(rng.integers(1, C + 1))
         d = esc.desc_of(L.spec)
         st = esc.escoin_sconv_pack(d, L.rowptr, L.colidx)
         try:
@@ -115,6 +129,53 @@ def test_plan_accepts_unsorted_rows_and_duplicates(oracle):
     assert np.all(np.abs(got - ref) <= 1e-6 * bound + 1e-12)
 
 
+def test_long_rows_are_split_over_waves(oracle):
+    """One CSR row far longer than a wave's fair share (here: dense, next to rows of a few
+    nonzeros) is split over several waves of its workgroup, whose partial sums meet in LDS."""
+    rng = np.random.default_rng(5)
+    N, C, H, W, M = 2, 16, 9, 9, 12
+    w = np.where(rng.random((M, C, 3, 3)) < 0.04, rng.standard_normal((M, C, 3, 3)), 0.0).astype(np.float32)
+    w[3] = rng.standard_normal((C, 3, 3)).astype(np.float32)          # 144 nonzeros; the others about 6
+    w[7, :8] = rng.standard_normal((8, 3, 3)).astype(np.float32)      # 72
+    rowptr, colidx, value = wl.dense_to_csr(w)
+    x = rng.random((N, C, H, W), dtype=np.float32)
+    d = esc.make_desc(N, C, H, W, M, 3, 3, 1, 1)
+    st = esc.escoin_sconv_pack(d, rowptr, colidx)
+    for tune in (dict(K=2, WM=8, CC=4), dict(K=1, WM=16, CC=16), dict(K=4, WM=4, CC=5, WS=2)):
+        plan = esc.escoin_sconv_plan_build(d, rowptr, st, value, esc.make_tuning(**tune))
+        h = esc.plan_header(plan)
+        bins = h["n_mgroups"] * h["WM"]
+        rows = plan[h["off_perm"]:h["off_perm"] + 16 * bins * h["K"]].view(np.int32).reshape(-1, 4)
+        n_rows_of = np.bincount(rows[rows[:, 0] >= 0, 0], minlength=M)
+        assert n_rows_of[3] > max(2, tune.get("WS", 1)) and n_rows_of[3] > n_rows_of[0], (tune, n_rows_of)
+        assert h["max_regions"] >= n_rows_of[3] - 1
+        # the longest share of any accumulator row stays near a wave's fair share
+        nnz_row = np.diff(rowptr)
+        share = nnz_row / n_rows_of
+        fair = nnz_row.sum() / (h["n_mgroups"] * h["WM"])
+        assert share.max() <= max(2.0 * fair, nnz_row.max() / h["WM"] + 1), (tune, share.max(), fair)
+        got = simulate(plan, x, M)
+        ref, bound = oracle.conv(x, w, 1, 1)
+        assert np.all(np.abs(got - ref) <= 1e-6 * bound + 1e-12), tune
+
+
+def test_explicit_zeros_get_no_record(oracle):
+    """An explicit zero in the CSR adds nothing to any sum (the definition skips it); the plan
+    gives it no record, so it cannot turn a non-finite input into NaN either."""
+    L = wl.custom_layer(2, 4, 6, 6, 3, 3, 3, 1, 1, 0.5, seed=8)
+    value = L.value.copy()
+    value[::3] = 0.0
+    d = esc.desc_of(L.spec)
+    st = esc.escoin_sconv_pack(d, L.rowptr, L.colidx)
+    plan = esc.escoin_sconv_plan_build(d, L.rowptr, st, value)
+    h = esc.plan_header(plan)
+    rec_val = plan[h["off_rec"]:h["off_rec"] + 8 * h["n_records"]].view(np.float32)[1::2]
+    assert np.count_nonzero(rec_val) == np.count_nonzero(value)
+    got = simulate(plan, L.input, 3)
+    ref, bound = oracle.conv(L.input, oracle.csr_to_dense(3, 4, 3, 3, L.rowptr, L.colidx, value), 1, 1)
+    assert np.all(np.abs(got - ref) <= 1e-6 * bound + 1e-12)
+
+
 def test_rows_are_dealt_out_balanced():
     L = wl.make_layer("S80skew", with_input=False)
     d = esc.desc_of(L.spec)
@@ -122,7 +183,7 @@ def test_rows_are_dealt_out_balanced():
     plan = esc.escoin_sconv_plan_build(d, L.rowptr, st, L.value)
     h = esc.plan_header(plan)
     bins = h["n_mgroups"] * h["WM"]
-    perm = plan[h["off_perm"]:h["off_perm"] + 4 * bins * h["K"]].view(np.int32).reshape(bins, h["K"])
+    perm = plan[h["off_perm"]:h["off_perm"] + 16 * bins * h["K"]].view(np.int32).reshape(bins, h["K"], 4)[:, :, 0]
     nnz_row = np.diff(L.rowptr)
     load = np.array([nnz_row[p[p >= 0]].sum() for p in perm])
     assert load.max() <= 1.45 * load.mean()        # rows alone: max/mean = 5.0
