@@ -200,11 +200,16 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
     static const int kPairs[7][2] = {{4, 2}, {2, 2}, {4, 1}, {2, 1}, {1, 1}, {1, 2}, {8, 1}};
     const int pitch = image_pitch(d, 1);
     const int img_groups = ceil_div(d.E * pitch, 4);
-    int bestK = 2, bestQ = 1, bestTH = d.E, bestNB = 1, bestWM = 1;
+    int bestK = 2, bestQ = 1, bestTH = d.E, bestNB = 1, bestWM = 1, bestWS = 1;
     double best_score = -1.0;
     static const int kWaves[5] = {16, 12, 8, 6, 4};
     static const double kStageShare[5] = {1.0, 1.02, 1.08, 1.2, 1.4};
+    // Splitting every channel over WS waves multiplies the workgroups by WS at the same K and
+    // Q: what a launch with too few workgroups for the compute units needs (small batches).
+    for (int WS = 1; WS <= 16; WS *= 2)
     for (int i = 0; i < 7 * 5; ++i) {
+        if (t && t->WS > 0 && WS != 1) continue;  // the caller fixed it: one pass
+        const int ws = (t && t->WS > 0) ? t->WS : WS;
         const int K = kPairs[i / 5][0], Q = kPairs[i / 5][1];
         if (t && t->K > 0 && t->K != K) continue;
         if (t && t->Q > 0 && t->Q != Q) continue;
@@ -219,12 +224,17 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
             if (i % 5) continue;
             WM = t->WM;
             stage_share = 1.0;
-        } else if (WM > ceil_div(d.M, K)) {
-            if (i % 5 + 1 < 5 && kWaves[i % 5 + 1] >= ceil_div(d.M, K)) continue;
-            WM = ceil_div(d.M, K);
+        } else if (WM > ceil_div(d.M * ws, K)) {
+            if (i % 5 + 1 < 5 && kWaves[i % 5 + 1] >= ceil_div(d.M * ws, K)) continue;
+            WM = ceil_div(d.M * ws, K);
         }
+        if (ws > WM) continue;
         const int wave_groups = kRunLanes * Q;  // groups one wave can own
-        const int mgroups = ceil_div(d.M, K * WM);
+        const int mgroups = ceil_div(d.M * ws, K * WM);
+        // a wave's share of its K rows, with a little lost to shorter record segments, and the
+        // pass that adds the partial sums
+        const double split = ws == 1 ? 1.0 : (1.0 + 0.15 * std::log2((double)ws)) / ws;
+        const double merge = ws == 1 ? 0.0 : 0.25;
         auto consider = [&](int TH, int NB) {
             const long long wgs = (long long)ceil_div(d.E, TH) * ceil_div(d.N, NB) * mgroups;
             // the launch deals the workgroups out evenly over the 8 XCDs of 32 compute units
@@ -240,13 +250,15 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
             const int per_simd = ceil_div(WM * WQ, 4);
             const double crowd = per_simd >= 4 ? 1.0 : (per_simd == 3 ? 0.9 : 0.8);
             const double row_cost = Q == 2 ? (NB == 1 ? 1.75 : 1.9) : 1.0;
-            const double cost = rounds * (0.6 + K * row_cost * crowd / chunk) * stage_share;
+            const double cost = rounds * (0.6 + merge + K * split * row_cost * crowd / chunk) * stage_share;
             const double score = 1.0 / cost * (1.0 + 1e-3 * K);
             if (score > best_score) {
-                best_score = score; bestK = K; bestQ = Q; bestTH = TH; bestNB = NB; bestWM = WM;
+                best_score = score; bestK = K; bestQ = Q; bestTH = TH; bestNB = NB; bestWM = WM; bestWS = ws;
             }
         };
-        if (img_groups <= wave_groups) {  // whole images: NB of them per workgroup
+        if (t && (t->NB > 0 || t->TH > 0)) {  // the caller fixed the tile
+            consider(t->TH > 0 ? std::min(t->TH, d.E) : d.E, t->NB > 0 ? t->NB : 1);
+        } else if (img_groups <= wave_groups) {  // whole images: NB of them per workgroup
             int nb_max = 1;
             while (nb_max < d.N && lane_entries(d, nb_max + 1, d.E) - 2 <= wave_groups) ++nb_max;
             for (int NB = nb_max; NB >= 1; --NB) {
@@ -270,7 +282,7 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
     h->TH = (t && t->TH > 0) ? t->TH : bestTH;
     h->NB = (t && t->NB > 0) ? t->NB : ((t && t->TH > 0 && t->TH < d.E) ? 1 : bestNB);
     h->WM = (t && t->WM > 0) ? t->WM : bestWM;
-    h->WS = (t && t->WS > 0) ? t->WS : 1;
+    h->WS = (t && t->WS > 0) ? t->WS : bestWS;
     h->CC0 = (t && t->CC0 > 0) ? t->CC0 : 0;
     if (t && t->CC > 0) {
         h->CC = t->CC;
@@ -287,29 +299,6 @@ void choose_defaults(const Dims& d, const escoin_sconv_tuning* t, PlanHeader* h)
             h->CC = 1;
         }
     }
-}
-
-// Splitting the input channels of a tile over CS workgroups (which then add their partial sums
-// with atomics) pays only when the launch would otherwise leave most compute units without
-// a workgroup: small batches of small images.  Every workgroup keeps at least two chunks of
-// at least eight channels, and the chunk length is evened out so that all get the same number.
-void choose_split(const Dims& d, bool auto_cc, PlanHeader* h) {
-    Geometry g;
-    PlanHeader probe = *h;
-    probe.CS = 1;
-    h->CS = 1;
-    if (derive(d, &probe, &g) != ESCOIN_OK) return;
-    const long long wgs = (long long)probe.n_tiles * ceil_div(d.N, probe.NB) * probe.n_mgroups;
-    if (wgs > 96) return;
-    int cs = (int)std::min<long long>(192 / wgs, d.C / 16);
-    if (!auto_cc) cs = std::min(cs, probe.n_chunks / 2);
-    if (cs < 2) return;
-    if (auto_cc) {
-        const int chunks = cs * std::max(2, ceil_div(probe.n_chunks, cs));
-        h->CC = ceil_div(d.C, chunks);
-        h->CC = std::min(h->CC, probe.CC);
-    }
-    h->CS = cs;
 }
 
 struct RowNz {
@@ -820,7 +809,6 @@ int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_
     const bool auto_cs = !(tuning && tuning->CS > 0);
     h.CS = auto_cs ? 1 : tuning->CS;
     for (;;) {
-        if (auto_cs) choose_split(d, auto_cc, &h);
         // h.CC is the longest chunk that fits; the chunks of this attempt are evened out below it.
         // (A short first chunk, CC0 < CC, is the caller's choice: measured on the bundled layers
         // it gains 3-4 % when a layer runs alone with its input in the caches and loses 1-3 %
@@ -842,6 +830,9 @@ int build_plan(const escoin_conv_desc* desc, const int32_t* rowptr, const int32_
             h.NB = h.NB / 2;
         } else if (auto_tile && h.TH > 1) {
             h.TH = (h.TH + 1) / 2;
+        } else if (!(tuning && tuning->WM > 0) && h.WM > 1) {  // too many waves for this tile
+            h.WM = h.WM / 2;
+            if (!(tuning && tuning->WS > 0)) h.WS = std::min(h.WS, h.WM);
         } else {
             return rc;
         }

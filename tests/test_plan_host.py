@@ -141,7 +141,7 @@ def test_long_rows_are_split_over_waves(oracle):
     x = rng.random((N, C, H, W), dtype=np.float32)
     d = esc.make_desc(N, C, H, W, M, 3, 3, 1, 1)
     st = esc.escoin_sconv_pack(d, rowptr, colidx)
-    for tune in (dict(K=2, WM=8, CC=4), dict(K=1, WM=16, CC=16), dict(K=4, WM=4, CC=5, WS=2)):
+    for tune in (dict(K=2, WM=8, CC=4, WS=1), dict(K=1, WM=16, CC=16, WS=1), dict(K=4, WM=4, CC=5, WS=2)):
         plan = esc.escoin_sconv_plan_build(d, rowptr, st, value, esc.make_tuning(**tune))
         h = esc.plan_header(plan)
         bins = h["n_mgroups"] * h["WM"]
