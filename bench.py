@@ -1,16 +1,25 @@
 #!/usr/bin/env python3
 """Throughput of the direct sparse convolution hot path on one MI355X.
 
-A step is one pass of the whole hot path (pad_in + sconv, every layer of the workload) over
-one batch of seeded synthetic input already resident in HBM.  The default workload is the
-ResNet-50-style set of 3x3 layers at 80 % weight sparsity, batch 32 (the layers the stated
-target is quoted on).  Prints ONE JSON line: effective GFLOP/s counted as 2*nnz*E*F*N flops
-per layer, the roofline of the dominant kernel (HIP-event durations measured here), and the
-CPU oracle timed on a bounded sample of the same workload.
+A step is one pass of the whole hot path over one batch of seeded synthetic input already
+resident in HBM: every layer of the workload through the LDS-tiled sconv, which pads while it
+stages (the fused form of pad_in + sconv).  The default workload is the ResNet-50-style set of
+3x3 layers at 80 % weight sparsity, batch 32 (the layers the stated target is quoted on).
+
+Prints ONE JSON line:
+  value            effective GFLOP/s (2*nnz*E*F*N flops per layer) over the timed steps, inputs
+                   warm in the Infinity Cache (every step touches the same buffers);
+  roofline         the kernel with the largest average duration: HIP-event durations taken here;
+  layers           per layer: mean and median kernel time warm, median cold (caches flushed by a
+                   large write before every step), both roofline fractions, and the paper's
+                   two-kernel dataflow (pad_in, then sconv on the padded array) timed beside it;
+  other_workloads  the remaining bundled workloads, shorter runs of the same measurement;
+  cpu_baseline     the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -18,8 +27,10 @@ import time
 
 import numpy as np
 
+ROOT = os.path.dirname(os.path.abspath(__file__))
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # 256 CU x 128 FMA/clk x 2.4 GHz x 2
+FLUSH_BYTES = 1 << 30            # written before every cold step: four times the Infinity Cache
 
 
 def parse():
@@ -28,16 +39,17 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet",
-                    help="one of workloads.CONFIG_LAYERS or a comma list of layer names")
+                    help="one of workloads.CONFIG_LAYERS or a comma list of layer names; `chain` "
+                         "feeds every layer's output (bias + ReLU fused) to the next layer")
     ap.add_argument("--path", default=os.environ.get("ESCOIN_BENCH_PATH", "auto"),
-                    choices=["auto", "direct", "tiled"], help="which sconv entry point to time")
+                    choices=["auto", "direct", "tiled"], help="which sconv entry point `value` times")
     ap.add_argument("--flags", type=int, default=0, help="1 = bias, 2 = relu (fused epilogue)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-images", type=int, default=0,
                     help="images per layer for the oracle sample (0 = auto, about 10-30 s)")
-    ap.add_argument("--others", action="store_true",
-                    help="after the timed workload, also time the other bundled workloads (50 steps "
-                         "each) and report their GFLOP/s under `other_workloads`")
+    ap.add_argument("--no-others", action="store_true", help="skip the other bundled workloads")
+    ap.add_argument("--no-two-kernel", action="store_true", help="skip the pad_in + sconv leg")
+    ap.add_argument("--no-cold", action="store_true", help="skip the flushed-cache timing")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a few launches of a plain copy of known size "
@@ -54,6 +66,81 @@ def algorithmic_bytes(L, two_kernel: bool) -> int:
     if two_kernel and s.pad > 0:
         b += 2 * 4 * s.N * s.C * s.Hp * s.Wp
     return b
+
+
+def kernel_source_hash() -> str:
+    """Identifies the code the recorded HBM counters were taken with."""
+    h = hashlib.sha256()
+    for f in ("sconv_tiled.hip", "plan.cpp", "plan.h"):
+        h.update(open(os.path.join(ROOT, "paper_1802_10280_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+TRAFFIC_KEYS = ("K", "Q", "B", "WM", "WS", "CC", "CC0", "NB", "TH", "CS", "VW", "WW")
+
+
+def measured_traffic(runner):
+    """HBM bytes one launch of this layer's tiled kernel moved, read plus written, as the
+    rocprofv3 FETCH_SIZE / WRITE_SIZE counters recorded it (profiles/hbm_traffic.json, written
+    from the counter runs summarised beside it).  None unless a record matches this layer,
+    batch size, every tiling knob and the kernel sources exactly."""
+    table = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if runner.path != "tiled" or not os.path.exists(table):
+        return None
+    doc = json.load(open(table))
+    if doc.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    h, s = runner.plan_info, runner.layer.spec
+    for rec in doc["records"]:
+        if (rec["layer"] == s.name and rec["N"] == s.N and rec["nnz"] == runner.layer.nnz
+                and all(rec["plan"].get(k) == h[k] for k in TRAFFIC_KEYS)):
+            return rec["read_bytes"] + rec["written_bytes"]
+    return None
+
+
+def make_runners(wl, LayerRunner, workload, path, flags):
+    """Layers and runners of a workload; `chain` links every output to the next input."""
+    names = wl.CONFIG_LAYERS.get(workload) or workload.split(",")
+    layers = [wl.make_layer(n) for n in names]
+    runners = []
+    for i, L in enumerate(layers):
+        d_in = runners[-1].d_out if (workload == "chain" and i) else None
+        runners.append(LayerRunner(L, path=path, flags=flags, d_in=d_in))
+    return names, layers, runners
+
+
+def time_kernels(torch, runners, steps, stream, flush=None):
+    """HIP-event duration (ms) of every library call of every step: [steps, calls].  Events go
+    on the stream the kernels are launched on.  With `flush`, a large buffer is overwritten
+    before every step so that the step finds neither its inputs nor its plans in any cache."""
+    nk = sum(len(r.kernels()) for r in runners)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(nk + 1)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    for k in range(steps):
+        if flush is not None:
+            flush.add_(1)
+        i = 0
+        evs[k][0].record(stream)
+        for r in runners:
+            for fn in r.kernels():
+                fn()
+                i += 1
+                evs[k][i].record(stream)
+    torch.cuda.synchronize()
+    return np.array([[evs[k][i].elapsed_time(evs[k][i + 1]) for i in range(nk)] for k in range(steps)])
+
+
+def wall_time(torch, runners, steps, warmup):
+    for _ in range(warmup):
+        for r in runners:
+            r.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for r in runners:
+            r.run()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
 
 
 def main():
@@ -73,15 +160,12 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    names = wl.CONFIG_LAYERS.get(args.workload) or args.workload.split(",")
-    layers = [wl.make_layer(n) for n in names]
-    runners = [LayerRunner(L, path=args.path, flags=args.flags) for L in layers]
+    flags = args.flags
+    if args.workload == "chain" and not flags:
+        flags = esc.F_BIAS | esc.F_RELU       # the layers of a chain hand post-ReLU maps on
+    names, layers, runners = make_runners(wl, LayerRunner, args.workload, args.path, flags)
     flops = [2.0 * L.nnz * L.spec.E * L.spec.F * L.spec.N for L in layers]
     stream = torch.cuda.current_stream()
-
-    def step():
-        for r in runners:
-            r.run()
 
     if args.traffic_probe:
         # the copy moves exactly 2 * 64 MiB: it calibrates what FETCH_SIZE / WRITE_SIZE read
@@ -89,62 +173,70 @@ def main():
         src = torch.ones(n, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         d = esc.make_desc(1, 1, 4096, 4096, 1, 1, 1, 1, 0)
+        direct = [LayerRunner(L, path="direct", flags=flags) for L in layers]
         for _ in range(3):
             esc.escoin_pad_in(d, src, dst)
-            step()
+            for r in runners:
+                r.run()
+            for r in direct:
+                r.run()
         torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": "done", "copy_bytes_read": 4 * n, "copy_bytes_written": 4 * n,
-                          "launch_order": ["copy"] + [L.spec.name for L in layers], "rounds": 3,
+                          "launch_order": ["copy"] + [L.spec.name for L in layers]
+                          + [f"{L.spec.name}:pad_in,{L.spec.name}:direct" for L in layers], "rounds": 3,
+                          "kernel_source_hash": kernel_source_hash(),
                           "layers": [{"layer": L.spec.name, "N": L.spec.N, "nnz": L.nnz,
                                       "kernel": r.sconv_kernel_name(),
-                                      "plan": {k: r.plan_info[k] for k in ("K", "Q", "B", "WM", "CC", "NB", "TH")}
+                                      "plan": {k: r.plan_info[k] for k in TRAFFIC_KEYS}
                                       if r.path == "tiled" else None}
                                      for L, r in zip(layers, runners)]}))
         return
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    value = sum(flops) / (dt / args.steps) / 1e9
+    # ---- value: wall clock over the timed steps (warm)
+    sec_per_step = wall_time(torch, runners, args.steps, args.warmup)
+    ms_per_step = sec_per_step * 1e3
+    value = sum(flops) / sec_per_step / 1e9
 
-    # Per-kernel durations with HIP events on the launch stream (torch's current stream is the
-    # one handed to the library), over a second run of the same steps.
-    nk = sum(len(r.kernels()) for r in runners)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(nk + 1)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    for k in range(args.steps):
-        i = 0
-        evs[k][0].record(stream)
-        for r in runners:
-            for fn in r.kernels():
-                fn()
-                i += 1
-                evs[k][i].record(stream)
-    torch.cuda.synchronize()
-    dur = np.array([[evs[k][i].elapsed_time(evs[k][i + 1]) for i in range(nk)]
-                    for k in range(args.steps)])          # ms
-    avg_ms = dur.mean(axis=0)
+    # ---- per-kernel durations, warm: a second run of the same steps with events
+    dur = time_kernels(torch, runners, args.steps, stream)
+    avg_ms, med_ms = dur.mean(axis=0), np.median(dur, axis=0)
+    # ---- cold: every step starts from flushed caches (at least 20 steps for the median)
+    cold_ms = None
+    if not args.no_cold:
+        flush = torch.zeros(FLUSH_BYTES // 4, dtype=torch.float32, device="cuda")
+        cold_ms = np.median(time_kernels(torch, runners, max(20, min(args.steps, 50)), stream, flush), axis=0)
+        del flush
+    # ---- the paper's two-kernel dataflow on the same layers: pad_in, then sconv on the padded array
+    two = None
+    if not args.no_two_kernel and runners[0].path == "tiled":
+        direct = []
+        for i, L in enumerate(layers):
+            d_in = direct[-1].d_out if (args.workload == "chain" and i) else None
+            direct.append(LayerRunner(L, path="direct", flags=flags, d_in=d_in))
+        n2 = max(20, min(args.steps, 30))
+        for _ in range(3):
+            for r in direct:
+                r.run()
+        two = np.median(time_kernels(torch, direct, n2, stream), axis=0).reshape(len(layers), 2)
+        del direct
 
     rows, i = [], 0
-    for L, r, fl in zip(layers, runners, flops):
+    for li, (L, r, fl) in enumerate(zip(layers, runners, flops)):
         names_k = r.kernel_names()
         t = {nm: float(avg_ms[i + j]) for j, nm in enumerate(names_k)}
+        tm = {nm: float(med_ms[i + j]) for j, nm in enumerate(names_k)}
+        tc = {nm: float(cold_ms[i + j]) for j, nm in enumerate(names_k)} if cold_ms is not None else None
         i += len(names_k)
-        t_sconv = t["sconv"]
-        t_all = sum(t.values())
+        t_sconv, t_all = t["sconv"], sum(t.values())
         comp = algorithmic_bytes(L, two_kernel=False)
         moved = algorithmic_bytes(L, two_kernel="pad_in" in t)
         t_alu = fl / (FP32_VECTOR_PEAK_TFLOPS * 1e12) * 1e3
         t_hbm = comp / (HBM_PEAK_GBPS * 1e9) * 1e3
-        rows.append({
+        row = {
             "layer": L.spec.name, "kernel": r.sconv_kernel_name(), "nnz": L.nnz,
             "us_pad_in": round(t.get("pad_in", 0.0) * 1e3, 2), "us_sconv": round(t_sconv * 1e3, 2),
+            "us_sconv_median": round(tm["sconv"] * 1e3, 2),
+            "us_layer_cold_median": round(sum(tc.values()) * 1e3, 2) if tc else None,
             "gflops_sconv": round(fl / t_sconv / 1e6, 1), "gflops_layer": round(fl / t_all / 1e6, 1),
             "gbps_compulsory": round(comp / t_all / 1e6, 1),
             "gbps_method": round(moved / t_all / 1e6, 1),
@@ -152,11 +244,27 @@ def main():
             "alu_frac": round(fl / t_sconv / 1e9 / FP32_VECTOR_PEAK_TFLOPS, 4),
             "binding": "alu" if t_alu >= t_hbm else "hbm",
             "binding_frac": round(max(t_alu, t_hbm) / t_all, 4),
-        })
+        }
+        if tc:
+            row["hbm_frac_cold"] = round(comp / sum(tc.values()) / 1e6 / HBM_PEAK_GBPS, 4)
+        if two is not None:
+            s = L.spec
+            t_pad, t_dir = float(two[li][0]), float(two[li][1])
+            pad_bytes = 4 * s.N * s.C * (s.H * s.W + s.Hp * s.Wp)
+            row["two_kernel"] = {
+                "us_pad_in": round(t_pad * 1e3, 2), "us_sconv": round(t_dir * 1e3, 2),
+                "pad_in_gbps": round(pad_bytes / t_pad / 1e6, 1),
+                "pad_in_hbm_frac": round(pad_bytes / t_pad / 1e6 / HBM_PEAK_GBPS, 4),
+                "gflops_sconv": round(fl / t_dir / 1e6, 1),
+                "gflops_layer": round(fl / (t_pad + t_dir) / 1e6, 1),
+                "gbps_method": round(algorithmic_bytes(L, True) / (t_pad + t_dir) / 1e6, 1),
+            }
         # achieved GB/s: HBM-side bytes the counters recorded for this layer and tiling, if any
-        moved_hw = r.measured_traffic()
-        rows[-1]["traffic_bytes"] = moved_hw
-        rows[-1]["gbps_measured"] = round(moved_hw / t_sconv / 1e6, 1) if moved_hw else None
+        moved_hw = measured_traffic(r)
+        row["traffic_bytes"] = moved_hw
+        row["gbps_measured"] = round(moved_hw / t_sconv / 1e6, 1) if moved_hw else None
+        rows.append(row)
+
     dom = max(range(len(rows)), key=lambda k: rows[k]["us_sconv"])
     Ld, rd = layers[dom], rows[dom]
     if rd["binding"] == "alu":
@@ -168,44 +276,52 @@ def main():
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4)}
     roofline.update({"kernel": rd["kernel"], "layer": rd["layer"], "avg_us": rd["us_sconv"],
-                     "traffic": runners[dom].measured_traffic()})
+                     "median_us": rd["us_sconv_median"], "traffic": measured_traffic(runners[dom])})
 
+    fused = runners[0].path == "tiled"
     out = {
-        "metric": "effective GFLOP/s (2*nnz MACs) over pad_in+sconv of every layer; HBM GB/s per layer in `layers`",
+        "metric": ("effective GFLOP/s (2*nnz MACs) of the sparse convolution of every layer"
+                   + (", padding fused into the tiled sconv" if fused else ", pad_in + sconv")
+                   + "; HBM GB/s per layer in `layers`"),
         "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: " + ",".join(n for n in names),
                    "batch": layers[0].spec.N, "sparsity": layers[0].spec.sparsity,
-                   "path": runners[0].path, "flags": args.flags},
-        "hbm_gbps_compulsory": round(sum(algorithmic_bytes(L, False) for L in layers)
-                                     / (dt / args.steps) / 1e9, 1),
+                   "path": runners[0].path, "flags": flags, "cache_state": "warm (Infinity Cache)"},
+        "hbm_gbps_compulsory": round(sum(algorithmic_bytes(L, False) for L in layers) / sec_per_step / 1e9, 1),
+        "value_median_kernels": round(sum(flops) / float(med_ms.sum()) / 1e6, 1),
         "roofline": roofline,
         "layers": rows,
     }
+    if cold_ms is not None:
+        out["cold"] = {"gflops": round(sum(flops) / float(cold_ms.sum()) / 1e6, 1),
+                       "us_per_step_median": round(float(cold_ms.sum()) * 1e3, 2),
+                       "how": f"{FLUSH_BYTES >> 20} MiB overwritten before every step; sum of per-kernel medians"}
+    if two is not None:
+        out["two_kernel"] = {"gflops": round(sum(flops) / float(two.sum()) / 1e6, 1),
+                             "us_per_step_median": round(float(two.sum()) * 1e3, 2),
+                             "what": "pad_in, then the general sconv on the padded array (Section 4.2's dataflow)"}
 
-    if args.others:
-        # context only: the same measurement, shorter, on the other bundled workloads
+    if not args.no_others:
+        # the same measurement, shorter, on the other bundled workloads
         del runners
         others = {}
-        for w, ns in wl.CONFIG_LAYERS.items():
+        for w in wl.CONFIG_LAYERS:
             if w == args.workload:
                 continue
-            ls = [wl.make_layer(n) for n in ns]
-            rs = [LayerRunner(L, path=args.path, flags=args.flags) for L in ls]
-            fl = sum(2.0 * L.nnz * L.spec.E * L.spec.F * L.spec.N for L in ls)
-            for _ in range(5):
-                for r in rs:
-                    r.run()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(50):
-                for r in rs:
-                    r.run()
-            torch.cuda.synchronize()
-            t = (time.perf_counter() - t0) / 50
-            others[w] = {"gflops": round(fl / t / 1e9, 1), "ms_per_step": round(t * 1e3, 4),
-                         "layers": ",".join(ns)}
+            fl_w = esc.F_BIAS | esc.F_RELU if w == "chain" else args.flags
+            ns, ls, rs = make_runners(wl, LayerRunner, w, args.path, fl_w)
+            fl = [2.0 * L.nnz * L.spec.E * L.spec.F * L.spec.N for L in ls]
+            sec = wall_time(torch, rs, 50, 5)
+            med = np.median(time_kernels(torch, rs, 30, stream), axis=0)
+            per, j = {}, 0
+            for L, r in zip(ls, rs):
+                n_k = len(r.kernel_names())
+                per[L.spec.name] = round(float(med[j:j + n_k].sum()) * 1e3, 2)
+                j += n_k
+            others[w] = {"gflops": round(sum(fl) / sec / 1e9, 1), "ms_per_step": round(sec * 1e3, 4),
+                         "us_median": per}
             del rs, ls
         out["other_workloads"] = others
 

@@ -9,7 +9,9 @@ from . import binding as B
 
 
 class LayerRunner:
-    def __init__(self, layer, path: str = "auto", flags: int = 0, stream=None, tuning=None):
+    def __init__(self, layer, path: str = "auto", flags: int = 0, stream=None, tuning=None, d_in=None):
+        """d_in: a device tensor to read the input from instead of uploading the layer's own
+        (the previous layer's output when layers are chained)."""
         import torch
         self.layer, self.flags, self.stream = layer, flags, stream
         s = layer.spec
@@ -22,7 +24,11 @@ class LayerRunner:
         self.d_colidx = up(self.stretched) if nz else torch.zeros(1, dtype=torch.int32, device=dev)
         self.d_value = up(layer.value) if nz else torch.zeros(1, dtype=torch.float32, device=dev)
         self.d_bias = up(layer.bias) if layer.bias is not None else None
-        self.d_in = up(layer.input)
+        if d_in is not None:
+            assert tuple(d_in.shape) == (s.N, s.C, s.H, s.W) and d_in.dtype == torch.float32
+            self.d_in = d_in
+        else:
+            self.d_in = up(layer.input)
         self.d_padded = torch.empty(B.escoin_padded_elems(self.desc), dtype=torch.float32, device=dev)
         self.d_out = torch.empty((s.N, s.M, s.E, s.F), dtype=torch.float32, device=dev)
         self.path = "tiled" if path == "auto" else path
@@ -71,21 +77,3 @@ class LayerRunner:
         for k in self.kernels():
             k()
         return self.d_out
-
-    def measured_traffic(self):
-        """HBM bytes one launch of this layer's sconv kernel moved, read plus written, as the
-        rocprofv3 FETCH_SIZE / WRITE_SIZE counters recorded it (hbm_traffic.json beside this
-        file, written from the counter runs whose summary sits under profiles/).  None when no
-        record matches this layer, batch size and tiling exactly."""
-        import json, os
-        if self.path != "tiled":
-            return None
-        table = os.path.join(os.path.dirname(os.path.abspath(__file__)), "hbm_traffic.json")
-        if not os.path.exists(table):
-            return None
-        h, s = self.plan_info, self.layer.spec
-        for rec in json.load(open(table))["records"]:
-            if (rec["layer"] == s.name and rec["N"] == s.N and rec["nnz"] == self.layer.nnz
-                    and all(rec["plan"][k] == h[k] for k in rec["plan"])):
-                return rec["read_bytes"] + rec["written_bytes"]
-        return None

@@ -89,6 +89,8 @@ LAYERS = {
         _L("R14", 3, 2, 32, 256, 14, 256, 3, 1, 1, 0.80),
         _L("R7", 3, 3, 32, 512, 7, 512, 3, 1, 1, 0.80),
         _L("R56s2", 3, 4, 32, 128, 56, 128, 3, 2, 1, 0.80),
+        # head of a three-layer chain (C56 -> R56s2 -> R28): each output is the next input
+        _L("C56", 3, 5, 32, 64, 56, 128, 3, 1, 1, 0.80),
         _L("S50", 4, 0, 64, 256, 28, 256, 3, 1, 1, 0.50),
         _L("S70", 4, 1, 64, 256, 28, 256, 3, 1, 1, 0.70),
         _L("S80", 4, 2, 64, 256, 28, 256, 3, 1, 1, 0.80),
@@ -105,6 +107,7 @@ CONFIG_LAYERS = {
     "alexnet_b64": ["A1b64", "A2b64", "A3b64"],
     "googlenet": ["G1", "G3", "G5"],
     "resnet": ["R56", "R28", "R14", "R7", "R56s2"],
+    "chain": ["C56", "R56s2", "R28"],
     "sweep": ["S50", "S70", "S80", "S90", "S95", "S80skew", "S80skewperm"],
 }
 

@@ -90,3 +90,24 @@ def sample_points(spec, k, seed):
     edge = [(n, m, h, w) for n in (0, spec.N - 1) for m in (0, spec.M - 1)
             for h in (0, spec.E - 1) for w in (0, spec.F - 1)]
     return np.concatenate([pts, np.array(edge)], axis=0).astype(np.int32)
+
+
+def seam_points(spec, plan_info, seed, pairs=24):
+    """Output elements on both sides of every seam of the tiling: the last row of a band and the
+    first row of the next (all columns), and, where several images share a tile, the images on
+    both sides of a tile boundary and the last image (whole maps), for `pairs` random (image,
+    channel) pairs each."""
+    rng = np.random.default_rng(seed)
+    TH, NB = plan_info["TH"], plan_info["NB"]
+    pts = []
+    rows = sorted({h for k in range(1, -(-spec.E // TH)) for h in (k * TH - 1, k * TH) if 0 <= h < spec.E})
+    for _ in range(pairs):
+        n, m = int(rng.integers(0, spec.N)), int(rng.integers(0, spec.M))
+        pts += [(n, m, h, w) for h in rows for w in range(spec.F)]
+    if NB > 1:
+        images = sorted({n for n in (NB - 1, NB, (spec.N // NB) * NB - 1, (spec.N // NB) * NB, spec.N - 1)
+                         if 0 <= n < spec.N})
+        for n in images:
+            for m in rng.integers(0, spec.M, size=max(1, pairs // 4)):
+                pts += [(n, int(m), h, w) for h in range(spec.E) for w in range(spec.F)]
+    return np.array(pts, dtype=np.int32).reshape(-1, 4)

@@ -9,7 +9,7 @@ import pytest
 import paper_1802_10280_amd as esc
 from paper_1802_10280_amd import workloads as wl
 
-from helpers import DeviceLayer, assert_within_bound, oracle_full, sample_points, to_dev
+from helpers import DeviceLayer, assert_within_bound, oracle_full, sample_points, seam_points, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -350,44 +350,59 @@ def test_tiled_plan_serves_other_batch_sizes(oracle):
 
 
 # ------------------------------------------------------------------ the paper-shaped layers
-FULL_WHOLE = ["A1b1", "A2b1", "A3b1"]                      # oracle computes every element quickly
-FULL_SAMPLED = ["R56", "R28", "R14", "R7", "R56s2", "G1", "G3", "G5", "A2b64", "S80", "S95",
-                "S80skew", "S80skewperm", "S50"]
+# the oracle computes every element of these within seconds: whole output, both entry points
+FULL_WHOLE = ["A1b1", "A2b1", "A3b1", "R56", "R28", "R14", "R7", "R56s2", "C56", "G1", "G3", "G5", "S90", "S95"]
+# the largest ones: sampled outputs plus every seam of the tiling
+FULL_SAMPLED = ["A2b64", "S80", "S80skew", "S80skewperm", "S50", "S70"]
 
 
 @pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("name", FULL_WHOLE)
 def test_full_size_layers_whole_output(oracle, name, path):
+    """The bench's layers at the bench's sizes and launch configuration, every output element."""
     print("sconv full", name, path, flush=True)
     L = wl.make_layer(name)
-    got = DeviceLayer(esc, L).run(path, 0)
-    ref, bound = oracle_full(oracle, L, 0)
+    s = L.spec
+    dl = DeviceLayer(esc, L)
+    flags = esc.F_BIAS | esc.F_RELU
+    got = dl.run(path, flags)
+    if path == "direct":
+        assert dl.d_padded.cpu().numpy().tobytes() == oracle.pad_input(L.input, s.pad).tobytes()
+    ref, bound = oracle_full(oracle, L, flags)
     assert_within_bound(got, ref, bound, name)
+    del ref, bound
+    if name in ("R56", "R7", "A2b1"):         # once more without the epilogue
+        ref, bound = oracle_full(oracle, L, 0)
+        assert_within_bound(dl.run(path, 0), ref, bound, name + " plain")
 
 
 @pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("name", FULL_SAMPLED)
 def test_full_size_layers_sampled_outputs(oracle, name, path):
-    """At the bench's sizes the oracle evaluates sampled output elements one by one; padding is
-    checked in full (bit-exact) and the output must hold no unwritten element."""
+    """Where the whole output would take the oracle too long: 100 000 random output elements,
+    every element on a seam of the tiling, the padded array in full (bit-exact), no unwritten
+    element, and the all-ones row-sum property over the whole output."""
     print("sconv full sampled", name, path, flush=True)
     L = wl.make_layer(name)
     s = L.spec
     dl = DeviceLayer(esc, L)
-    got = dl.run(path, esc.F_BIAS | esc.F_RELU)
+    flags = esc.F_BIAS | esc.F_RELU
+    got = dl.run(path, flags)
     assert np.isfinite(got).all()
     if path == "direct":
         pad_ref = oracle.pad_input(L.input, s.pad)
         assert dl.d_padded.cpu().numpy().tobytes() == pad_ref.tobytes()
-    pts = sample_points(s, 4000, seed=s.seed)
+        del pad_ref
+        plan_info = esc.plan_header(esc.escoin_sconv_plan_build(dl.desc, L.rowptr, dl.stretched, L.value))
+    else:
+        plan_info = esc.plan_header(dl.plan)
+    pts = np.concatenate([sample_points(s, 100_000, seed=s.seed), seam_points(s, plan_info, seed=s.seed + 1)])
     Wd = oracle.csr_to_dense(s.M, s.C, s.R, s.S, L.rowptr, L.colidx, L.value)
-    ref, bound = oracle.conv_points(L.input, Wd, pts, s.stride, s.pad, bias=L.bias,
-                                    flags=esc.F_BIAS | esc.F_RELU)
+    ref, bound = oracle.conv_points(L.input, Wd, pts, s.stride, s.pad, bias=L.bias, flags=flags)
     g = got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
     assert_within_bound(g, ref, bound, name)
     # whole-output property that holds at any size: an all-ones input turns every interior
     # output into the CSR row sum
-    import torch
     dl.d_in.fill_(1.0)
     got1 = dl.run(path, 0)
     rowsum = np.array([L.value[a:b].astype(np.float64).sum() for a, b in zip(L.rowptr[:-1], L.rowptr[1:])])
@@ -396,3 +411,53 @@ def test_full_size_layers_sampled_outputs(oracle, name, path):
     inner = got1[:, :, k:s.E - k, k:s.F - k] if k else got1
     err = np.abs(inner - rowsum[None, :, None, None])
     assert (err <= 1e-4 * rowabs[None, :, None, None] + 1e-30).all(), name
+
+
+# ------------------------------------------------------------------ layers chained on the device
+def _chain_check(oracle, layers, tunings=None):
+    """Runs the layers back to back on the device, each output (bias + ReLU fused) being the
+    next layer's input with nothing in between, and compares the last output with the oracle
+    applied layer by layer.  The bound is composed: a layer's own 1e-4 * sum|w*x| plus what the
+    deviation allowed on its input can grow to, sum|w| * tol_in (ReLU does not enlarge it)."""
+    import torch
+    from paper_1802_10280_amd.runner import LayerRunner
+    flags = esc.F_BIAS | esc.F_RELU
+    runners, x_ref, tol = [], layers[0].input.astype(np.float64), None
+    for i, L in enumerate(layers):
+        s = L.spec
+        runners.append(LayerRunner(L, path="tiled", flags=flags, tuning=(tunings or {}).get(i),
+                                   d_in=runners[-1].d_out if i else None))
+        Wd = oracle.csr_to_dense(s.M, s.C, s.R, s.S, L.rowptr, L.colidx, L.value)
+        x32 = x_ref.astype(np.float32)          # the oracle takes fp32 input, as the device does
+        y, bound = oracle.conv(x32, Wd, s.stride, s.pad, bias=L.bias, flags=flags)
+        own = 1e-4 * bound + np.abs(x_ref - x32).max() * np.abs(Wd).sum()   # + rounding of the fp32 hand-over
+        if tol is not None:
+            grown, _ = oracle.conv(tol.astype(np.float32), np.abs(Wd), s.stride, s.pad)
+            own = own + grown * (1 + 1e-6)
+        x_ref, tol = y, own
+    for r in runners:
+        r.run()
+    torch.cuda.synchronize()
+    got = runners[-1].d_out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all() and (got >= 0).all()
+    err = np.abs(got - x_ref)
+    assert (err <= tol).all(), (err.max(), float((err / np.maximum(tol, 1e-30)).max()))
+    # the intermediate maps were really written by the layers before: each equals its own run
+    assert float(np.abs(got).max()) > 0
+    return float((err / np.maximum(tol, 1e-30)).max())
+
+
+def test_two_and_three_layers_chained_small(oracle):
+    print("sconv chain small", flush=True)
+    a = wl.custom_layer(3, 6, 20, 22, 10, 3, 3, 1, 1, 0.6, seed=301, dist="normal")
+    b = wl.custom_layer(3, 10, 20, 22, 8, 3, 3, 2, 1, 0.5, seed=302, dist="normal")
+    c = wl.custom_layer(3, 8, 10, 11, 12, 1, 1, 1, 0, 0.5, seed=303, dist="normal")
+    _chain_check(oracle, [a, b])
+    _chain_check(oracle, [a, b, c], tunings={0: dict(K=2, Q=2, TH=7, CC=4), 1: dict(K=2, WM=4, WS=2)})
+
+
+def test_three_layers_chained_at_bench_size(oracle):
+    """The chain the bench times as `--workload chain`: C56 -> R56s2 (stride 2) -> R28 at batch
+    32, every output element of the last layer checked."""
+    print("sconv chain C56 -> R56s2 -> R28", flush=True)
+    _chain_check(oracle, [wl.make_layer(n) for n in wl.CONFIG_LAYERS["chain"]])
