@@ -1,6 +1,6 @@
 // sconv, general form: Algorithm 2 on the stretched CSR and the padded input array, with the
-// data-to-thread mapping of Section 3.2 (consecutive lanes own consecutive output positions)
-// and a workgroup per output channel (Section 3.3).  It accepts any filter size, stride and
+// data-to-thread mapping of Section 3.2 (consecutive lanes own consecutive output positions,
+// numbered through the images of the batch) and a workgroup per output channel (Section 3.3).  It accepts any filter size, stride and
 // CSR entry order.  The CSR row is wave-uniform, so its (offset, value) pairs travel through
 // the scalar data path instead of being staged in LDS; the input window is read through the
 // vector L1/L2, which plays the part of the read-only cache of Section 3.3.
@@ -11,42 +11,47 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kPix = 4;  // output positions per lane, kThreads apart (independent FMA chains)
 
+// A workgroup owns one output channel and kThreads * kPix output positions of a group of images:
+// the positions of the group's images are numbered through (image, h, w), so that small maps
+// fill the lanes as well as large ones.  Offsets inside a group fit 32 bits (the launch sizes the
+// groups for that).
 __global__ __launch_bounds__(kThreads) void sconv_direct_kernel(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
     const float* __restrict__ value, const float* __restrict__ padded, float* __restrict__ out,
-    const float* __restrict__ bias, uint32_t flags, int M, int E, int F, int Wp, int stride,
-    int img_elems /* C*Hp*Wp */) {
+    const float* __restrict__ bias, uint32_t flags, int N, int M, int E, int F, int Wp, int stride,
+    int img_elems /* C*Hp*Wp */, int group_images) {
     const int m = blockIdx.y;
     const int EF = E * F;
     const int j0 = rowptr[m], j1 = rowptr[m + 1];
     const float b = (flags & ESCOIN_F_BIAS) ? bias[m] : 0.0f;
-    {
-        const int n = blockIdx.z;
-        const float* __restrict__ img = padded + (size_t)n * img_elems;
-        int p[kPix];
-        int base[kPix];
-        float acc[kPix];
+    const int n_first = blockIdx.z * group_images;
+    const int n_here = min(group_images, N - n_first);
+    const uint32_t positions = (uint32_t)n_here * (uint32_t)EF;
+    const float* __restrict__ grp = padded + (size_t)n_first * img_elems;
+    uint32_t p[kPix], base[kPix];
+    float acc[kPix];
 #pragma unroll
-        for (int k = 0; k < kPix; ++k) {
-            p[k] = (blockIdx.x * kPix + k) * kThreads + threadIdx.x;
-            const int pc = p[k] < EF ? p[k] : 0;  // clamp: out-of-range lanes read a valid pixel
-            const int h = pc / F;
-            const int w = pc - h * F;
-            base[k] = h * stride * Wp + w * stride;  // f(0, h, w) on the padded pitch
-            acc[k] = b;
-        }
-        for (int j = j0; j < j1; ++j) {
-            const int off = colidx[j];
-            const float val = value[j];
+    for (int k = 0; k < kPix; ++k) {
+        p[k] = (blockIdx.x * kPix + k) * kThreads + threadIdx.x;
+        const uint32_t pc = p[k] < positions ? p[k] : 0;  // clamp: out-of-range lanes read a valid pixel
+        const uint32_t n = pc / (uint32_t)EF, pp = pc - n * (uint32_t)EF;
+        const uint32_t h = pp / (uint32_t)F, w = pp - h * (uint32_t)F;
+        base[k] = n * (uint32_t)img_elems + h * (uint32_t)(stride * Wp) + w * (uint32_t)stride;  // f(0, h, w) of image n
+        acc[k] = b;
+    }
+    for (int j = j0; j < j1; ++j) {
+        const uint32_t off = (uint32_t)colidx[j];
+        const float val = value[j];
 #pragma unroll
-            for (int k = 0; k < kPix; ++k) acc[k] = fmaf(val, img[off + base[k]], acc[k]);
-        }
-        float* __restrict__ o = out + ((size_t)n * M + m) * EF;
+        for (int k = 0; k < kPix; ++k) acc[k] = fmaf(val, grp[off + base[k]], acc[k]);
+    }
 #pragma unroll
-        for (int k = 0; k < kPix; ++k) {
-            float v = acc[k];
-            if (flags & ESCOIN_F_RELU) v = v > 0.0f ? v : 0.0f;
-            if (p[k] < EF) o[p[k]] = v;
+    for (int k = 0; k < kPix; ++k) {
+        float v = acc[k];
+        if (flags & ESCOIN_F_RELU) v = v > 0.0f ? v : 0.0f;
+        if (p[k] < positions) {
+            const uint32_t n = p[k] / (uint32_t)EF, pp = p[k] - n * (uint32_t)EF;
+            out[((size_t)(n_first + n) * M + m) * EF + pp] = v;
         }
     }
 }
@@ -58,15 +63,34 @@ namespace escoin {
 int launch_sconv_direct(const Dims& d, const int32_t* d_rowptr, const int32_t* d_colidx,
                         const float* d_value, const float* d_padded, float* d_out,
                         const float* d_bias, uint32_t flags, hipStream_t stream) {
-    const int EF = d.E * d.F;
-    const int per_block = kThreads * kPix;
-    // grid.y / grid.z carry M and N; both are far below the 65535 limit for any layer whose
-    // indices fit int32 here, but reject rather than fold silently
-    if (d.M > 65535 || d.N > 65535) return ESCOIN_ERANGE;
-    dim3 grid((EF + per_block - 1) / per_block, d.M, d.N);
+    const long long EF = (long long)d.E * d.F;
+    const long long img_elems = (long long)d.C * d.Hp * d.Wp;
+    // images per group: offsets inside a group (below group * img_elems, plus a nonzero's own
+    // offset below img_elems) and position numbers stay under 2^32
+    long long limit = std::max<long long>(1, std::min<long long>(d.N, ((1ll << 31) / img_elems)));
+    limit = std::max<long long>(1, std::min<long long>(limit, (1ll << 30) / EF));
+    // A group's padded input should stay in the L2s (4 MB per XCD) while all M output channels
+    // walk over it (the grid's slowest index is the group), yet its positions should fill the
+    // lanes of whole workgroups: among the group sizes up to 6 MB of input, the one that wastes
+    // the fewest lanes (the smaller one within 3 %).
+    const long long per_block = kThreads * kPix;
+    const long long most = std::max<long long>(1, std::min<long long>(limit, (6ll << 20) / (img_elems * 4)));
+    long long group = 1;
+    double best_fill = 0.0;
+    for (long long g = 1; g <= most; ++g) {
+        const long long n_groups = (d.N + g - 1) / g, even = (d.N + n_groups - 1) / n_groups;
+        if (even != g) continue;  // only sizes that split the batch evenly
+        const double fill = (double)(g * EF) / (double)(((g * EF + per_block - 1) / per_block) * per_block);
+        if (fill > best_fill * 1.03) { best_fill = fill; group = g; }
+    }
+    const long long groups = (d.N + group - 1) / group;
+    const long long bx = (group * EF + per_block - 1) / per_block;
+    // grid.y / grid.z carry M and the image groups; reject rather than fold silently
+    if (d.M > 65535 || groups > 65535 || bx > 0x7FFFFFFFll) return ESCOIN_ERANGE;
+    dim3 grid((unsigned)bx, d.M, (unsigned)groups);
     return launch(sconv_direct_kernel, grid, dim3(kThreads), 0, stream, d_rowptr, d_colidx, d_value,
-                  d_padded, d_out, d_bias, flags, d.M, d.E, d.F, d.Wp, d.stride,
-                  d.C * d.Hp * d.Wp);
+                  d_padded, d_out, d_bias, flags, d.N, d.M, d.E, d.F, d.Wp, d.stride,
+                  (int)img_elems, (int)group);
 }
 
 }  // namespace escoin
