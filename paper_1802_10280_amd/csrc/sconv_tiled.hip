@@ -48,7 +48,7 @@ struct TiledArgs {
     int N, C, HW, M, EF;
     int WM, WQ, CC, CC0, NB, CS, WW;
     int n_tiles, n_mgroups, n_chunks, n_in_tiles;
-    int plane_stride, P4, n_items, buf_floats, tail_floats, rec_buf_bytes, region_floats;
+    int plane_stride, P4, n_items, buf_floats, tail_floats, rec_buf_bytes, region_floats, used_slots;
     uint32_t flags;
 };
 
@@ -164,9 +164,16 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         const StageSlot* __restrict__ sl = a.stage + (size_t)tile * kMaxItemsPerThread * nthreads + tid;
         // words of images past the end of the batch (ragged last image group) are not staged
         const int src_end = min(a.NB, a.N - n0) * a.C * a.HW;
+        // Only the slots the tile uses are read, and where every run of four words is
+        // committed with one 16-byte LDS write only the run's first slot matters: the table is
+        // read by every workgroup, so for layers of few chunks it weighs as much as the input.
+        const bool run_heads_only = VW == 4 && a.WW == 4;
 #pragma unroll
         for (int j = 0; j < kMaxItemsPerThread; ++j) {
-            const StageSlot v = sl[(size_t)j * nthreads];
+            StageSlot v;
+            v.src = -1;
+            v.key = 0;
+            if (j < a.used_slots && (j % 4 == 0 || !run_heads_only)) v = sl[(size_t)j * nthreads];
             if (j % VW == 0) st_src[j / VW] = v.src < src_end ? v.src : -1;
             st_key[j] = v.key;
         }
@@ -229,12 +236,32 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
 
     // This workgroup's chunks: cs, cs + CS, ... (all of them unless the channels are split).
     fetch(cs, 0);
+    // With a single chunk to do, the output offsets are asked for now, next to the first
+    // fetch, instead of after it: one memory round trip less in a short launch.
+    const bool single_chunk = cs + a.CS >= a.n_chunks;
+    int early_dst[Q][4];
+    if (single_chunk) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int dd = -1;
+                if (pos0[q] >= 0 && n0 + nloc[q] < a.N) dd = a.dst_lut[(size_t)tile * a.P4 + pos0[q] + i];
+                early_dst[q][i] = dd;
+            }
+    }
     // The frame of zeros never changes: clear the window buffers and the tail once; from here
     // on only words that hold input are rewritten, chunk after chunk.
     for (int i = 4 * tid; i < 2 * a.buf_floats + a.tail_floats; i += 4 * nthreads)  // both are multiples of 4
         *(f4*)__builtin_assume_aligned(&lds[i], 16) = (f4)(0.0f);
     __syncthreads();
     commit(cs, 0);
+    if (single_chunk) {  // the staging registers are free for good: they take the output offsets
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) st_val[q * 4 + i] = __int_as_float(early_dst[q][i]);
+    }
     __builtin_amdgcn_s_waitcnt(0);  // this wave's record copies have landed
     __syncthreads();
 
@@ -388,7 +415,8 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         __syncthreads();
     }
     // the last chunk: nothing to fetch any more, so the staging registers take the output offsets
-    load_dst();
+    // (a workgroup with a single chunk has had them since its prologue)
+    if (it > 0) load_dst();
     compute(ch, it & 1, std::true_type{});
 
     // ---- channels split over several accumulator rows: the lending rows put their partial
@@ -552,6 +580,10 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     a.plane_stride = h.plane_stride; a.P4 = h.P4; a.n_items = h.n_items;
     a.buf_floats = h.buf_floats; a.tail_floats = h.tail_floats; a.rec_buf_bytes = h.rec_buf_bytes;
     a.region_floats = h.WQ * h.Q * 256;
+    {   // staging slots in use: the tile's runs of VW words are dealt to the threads in turn
+        const long long runs = ((long long)h.n_items * h.CC * h.NB + h.VW - 1) / h.VW;
+        a.used_slots = (int)std::min<long long>(kMaxItemsPerThread, (runs + threads - 1) / threads * h.VW);
+    }
     a.flags = flags;
 
     const size_t lds_bytes = (size_t)h.lds_bytes;
