@@ -18,10 +18,10 @@
  *     input dims.
  *   - oracle_pad: the zero-padded 1-D input array of Section 3.1 (the pad_in step of
  *     Section 4.2).
- *   - oracle_sconv_alg2: Algorithm 2 taken step by step (loops n, m, j, h, w; offset from
- *     colidx plus f(0,h,w)) on the stretched CSR and the padded array, fp64 accumulation.
- *     It must agree with oracle_conv; that agreement pins the readings of padding, stride
- *     and f(0,h,w).
+ *   - oracle_sconv_alg2: the layer in its stretched form (Section 3.1, the result of
+ *     Algorithm 2): per output element, the sum over the CSR row's entries of value times
+ *     the padded 1-D array at (stretched offset + f(0,h,w)), fp64 sum.  It must agree with
+ *     oracle_conv; that agreement pins the readings of padding, stride and f(0,h,w).
  *
  * All tensors are contiguous NCHW / MCRS, indices int32.
  */
@@ -182,31 +182,34 @@ int oracle_pad(int N, int C, int H, int W, int pad, const float *in, float *padd
     return 0;
 }
 
-/* Algorithm 2 as stated: for n, m, each nonzero j of row m: off = colidx'[j], val = value[j];
- * for h, w: out[n][m][h][w] += val * in[n][off + f(0,h,w)], with f(0,h,w) = h*stride*Wp +
- * w*stride on the padded array (image pitch C*Hp*Wp).  fp64 partial sums. */
+/* The stretched form of the layer (Section 3.1; the result Algorithm 2 produces): with the
+ * padded array P of one image flattened to 1-D, every output element is the sum, over the
+ * entries of CSR row m, of value * P[stretched offset + (h*stride)*Wp + w*stride].  Written per
+ * output element, like conv_point above but over the row's entries instead of over (c, r, s);
+ * fp64 sum.  It must agree with oracle_conv, which pins the padded dims in the offset, the
+ * stride on the output coordinate and the per-image pitch C*Hp*Wp. */
 int oracle_sconv_alg2(int N, int C, int H, int W, int M, int R, int S, int stride, int pad,
                       const int32_t *rowptr, const int32_t *stretched, const float *value,
                       const float *padded, float *out)
 {
     shape_t p = {N, C, H, W, M, R, S, stride, pad};
-    const int Hp = H + 2 * pad, Wp = W + 2 * pad;
+    const int Wp = W + 2 * pad;
     const int E = out_h(&p), F = out_w(&p);
-    const int64_t img = (int64_t)C * Hp * Wp;
+    const int64_t image_len = (int64_t)C * (H + 2 * pad) * Wp;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int n = 0; n < N; ++n) {
         for (int m = 0; m < M; ++m) {
-            double *acc = (double *)calloc((size_t)E * F, sizeof(double));
-            for (int32_t j = rowptr[m]; j < rowptr[m + 1]; ++j) {
-                int32_t off = stretched[j];
-                double val = (double)value[j];
-                for (int h = 0; h < E; ++h)
-                    for (int w = 0; w < F; ++w)
-                        acc[h * F + w] +=
-                            val * (double)padded[n * img + off + (int64_t)h * stride * Wp + w * stride];
+            const float *image = padded + n * image_len;
+            float *plane = out + ((int64_t)n * M + m) * E * F;
+            for (int h = 0; h < E; ++h) {
+                for (int w = 0; w < F; ++w) {
+                    const int64_t corner = (int64_t)h * stride * Wp + (int64_t)w * stride;
+                    double sum = 0.0;
+                    for (int32_t e = rowptr[m]; e < rowptr[m + 1]; ++e)
+                        sum += (double)value[e] * (double)image[stretched[e] + corner];
+                    plane[h * F + w] = (float)sum;
+                }
             }
-            for (int i = 0; i < E * F; ++i) out[((int64_t)n * M + m) * E * F + i] = (float)acc[i];
-            free(acc);
         }
     }
     return 0;
