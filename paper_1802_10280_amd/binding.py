@@ -206,7 +206,7 @@ PLAN_HEADER_FIELDS = (
      "lds_bytes", "nnz", "n_records"],
     ["off_items", "off_lanes", "off_dst_lut", "off_perm", "off_blk", "off_seg", "off_rec",
      "total_bytes"],
-    ["CS", "pitch1", "VW", "WW", "WS", "CC0", "zero_floats", "max_regions"])
+    ["CS", "pitch1", "VW", "WW", "WS", "CC0", "zero_floats", "max_regions", "MB"])
 
 
 def plan_header(plan: np.ndarray) -> dict:

@@ -91,6 +91,9 @@ struct PlanHeader {
     int32_t zero_floats; // floats at the end of every window buffer that stay zero: padding records
                          // point there, so they multiply zeros whatever the input holds
     int32_t max_regions; // most LDS regions (of WQ*Q*1024 bytes) a workgroup needs for partial sums
+    int32_t MB;          // the channel groups are cut into MB blocks; the launch order is (block,
+                         // tile, group in the block), so that an XCD meets 1/MB of the records
+    int32_t reserved[3];
 };
 
 }  // namespace escoin

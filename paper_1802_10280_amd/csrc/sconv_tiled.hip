@@ -46,7 +46,7 @@ struct TiledArgs {
     const uint32_t* seg;
     const uint32_t* rec;
     int N, C, HW, M, EF;
-    int WM, WQ, CC, CC0, NB, CS, WW;
+    int WM, WQ, CC, CC0, NB, CS, WW, MB;
     int n_tiles, n_mgroups, n_chunks, n_in_tiles;
     int plane_stride, P4, n_items, buf_floats, tail_floats, rec_buf_bytes, region_floats, used_slots;
     uint32_t flags;
@@ -138,9 +138,17 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     const int jq = jobs >> 3, jr = jobs & 7;
     if (slot_j >= jq + (xcd < jr ? 1 : 0)) return;  // whole workgroup leaves before any barrier
     const int job = xcd * jq + (xcd < jr ? xcd : jr) + slot_j;
-    const int cs = job % a.CS;
-    const int t_in = (job / a.CS) / a.n_mgroups;
-    const int mg = (job / a.CS) - t_in * a.n_mgroups;
+    // Job order: (block of channel groups, input tile, group inside the block, channel split).
+    // With one block this is tile-major; with MB blocks an XCD's range spans 1/MB of the groups,
+    // hence of the records, which matters where the records outweigh the input.
+    const int per_block = (a.n_mgroups + a.MB - 1) / a.MB;           // groups of a full block
+    const int block_jobs = a.n_in_tiles * per_block * a.CS;
+    const int blk_i = job / block_jobs;
+    const int in_block = min(per_block, a.n_mgroups - blk_i * per_block);  // the last block may be short
+    const int rj = job - blk_i * block_jobs;
+    const int cs = rj % a.CS;
+    const int t_in = (rj / a.CS) / in_block;
+    const int mg = blk_i * per_block + (rj / a.CS) - t_in * in_block;
     const int tile = t_in % a.n_tiles;
     const int n0 = (t_in / a.n_tiles) * a.NB;
 
@@ -550,7 +558,7 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
         h.n_chunks != (d.C <= h.CC0 ? 1 : 1 + (d.C - h.CC0 + h.CC - 1) / h.CC) ||
         h.WQ < 1 || h.WM < 1 || h.WS < 1 || h.WS > h.WM || h.tail_floats % 4 || h.rec_buf_bytes % 16 || h.front < 4 ||
         h.n_phases < 1 || h.n_phases > kMaxPhases || (h.VW != 1 && h.VW != 4) || (h.WW != 1 && h.WW != 4) || (h.WW == 4 && h.VW != 4) || h.CS < 1 || h.CS > h.n_chunks ||
-        h.zero_floats % 4 || h.zero_floats < h.P4 + 16 ||
+        h.zero_floats % 4 || h.zero_floats < h.P4 + 16 || h.MB < 1 || h.MB > 8 || h.MB > h.n_mgroups ||
         (long long)h.buf_floats != (long long)h.n_phases * h.CC * h.NB * h.plane_stride + h.zero_floats ||
         (long long)h.n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads ||
         (long long)h.buf_floats * 4 >= (1 << kKeyOffsetBits) || h.max_regions < 0 ||
@@ -571,7 +579,7 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     a.seg = (const uint32_t*)(base + h.off_seg);
     a.rec = (const uint32_t*)(base + h.off_rec);
     a.N = d.N; a.C = d.C; a.HW = d.H * d.W; a.M = d.M; a.EF = d.E * d.F;
-    a.WM = h.WM; a.WQ = h.WQ; a.CC = h.CC; a.CC0 = h.CC0; a.NB = h.NB; a.CS = h.CS; a.WW = h.WW;
+    a.WM = h.WM; a.WQ = h.WQ; a.CC = h.CC; a.CC0 = h.CC0; a.NB = h.NB; a.CS = h.CS; a.WW = h.WW; a.MB = h.MB;
     a.n_tiles = h.n_tiles; a.n_mgroups = h.n_mgroups; a.n_chunks = h.n_chunks;
     const long long n_in_tiles = (long long)h.n_tiles * ((d.N + h.NB - 1) / h.NB);
     const long long blocks = (n_in_tiles * h.n_mgroups * h.CS + 7) / 8 * 8;
