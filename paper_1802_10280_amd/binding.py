@@ -199,24 +199,23 @@ def escoin_sconv_forward_tiled(desc, plan_host: np.ndarray, d_plan, d_in, d_out,
                                             flags, _stream(stream)), "escoin_sconv_forward_tiled")
 
 
-PLAN_HEADER_FIELDS = (
-    ["magic", "version", "C", "H", "W", "M", "R", "S", "stride", "pad", "E", "F", "K", "Q", "B",
-     "WM", "WQ", "CC", "NB", "TH", "n_tiles", "n_mgroups", "n_chunks", "n_phases", "pitch", "front",
-     "rows_in", "plane_stride", "P4", "n_items", "buf_floats", "tail_floats", "rec_buf_bytes",
-     "lds_bytes", "nnz", "n_records"],
-    ["off_items", "off_lanes", "off_dst_lut", "off_perm", "off_blk", "off_seg", "off_rec",
-     "total_bytes"],
-    ["CS", "pitch1", "VW", "WW", "WS", "CC0", "zero_floats", "max_regions", "MB"])
+class _PlanHeader(ctypes.Structure):
+    """Mirror of the plan blob's header (csrc/plan.h), for diagnostics, tests and the bench."""
+    _fields_ = ([("magic", ctypes.c_uint32), ("version", ctypes.c_uint32)]
+                + [(k, ctypes.c_int32) for k in (
+                    "C", "H", "W", "M", "R", "S", "stride", "pad", "E", "F", "K", "Q", "B", "WM", "WQ",
+                    "CC", "NB", "TH", "n_tiles", "n_mgroups", "n_chunks", "n_phases", "pitch", "front",
+                    "rows_in", "plane_stride", "P4", "n_items", "buf_floats", "tail_floats",
+                    "rec_buf_bytes", "lds_bytes", "nnz", "n_records")]
+                + [(k, ctypes.c_uint64) for k in (
+                    "off_items", "off_lanes", "off_dst_lut", "off_perm", "off_blk", "off_seg", "off_rec",
+                    "total_bytes")]
+                + [(k, ctypes.c_int32) for k in (
+                    "CS", "pitch1", "VW", "WW", "WS", "CC0", "zero_floats", "max_regions", "MB", "n_dma")]
+                + [("off_dma", ctypes.c_uint64), ("off_zero", ctypes.c_uint64)])
 
 
 def plan_header(plan: np.ndarray) -> dict:
     """Decodes the (opaque) plan header for diagnostics, tests and the bench's reporting."""
-    n32 = len(PLAN_HEADER_FIELDS[0])
-    a = plan[:n32 * 4].view(np.int32)
-    b = plan[n32 * 4:n32 * 4 + 8 * len(PLAN_HEADER_FIELDS[1])].view(np.uint64)
-    h = {k: int(v) for k, v in zip(PLAN_HEADER_FIELDS[0], a)}
-    h.update({k: int(v) for k, v in zip(PLAN_HEADER_FIELDS[1], b)})
-    n64 = len(PLAN_HEADER_FIELDS[1])
-    c = plan[n32 * 4 + 8 * n64:n32 * 4 + 8 * n64 + 4 * len(PLAN_HEADER_FIELDS[2])].view(np.int32)
-    h.update({k: int(v) for k, v in zip(PLAN_HEADER_FIELDS[2], c)})
-    return h
+    h = _PlanHeader.from_buffer_copy(plan[:ctypes.sizeof(_PlanHeader)].tobytes())
+    return {k: int(getattr(h, k)) for k, _ in _PlanHeader._fields_}

@@ -39,6 +39,7 @@ namespace escoin {
 
 bool tiled_variant_exists(int K, int Q, int B);       // sconv_tiled.hip
 bool tiled_wide_staging_exists(int K, int Q, int B);  // sconv_tiled.hip
+bool tiled_dma_staging_exists(int K, int Q, int B);   // sconv_tiled.hip
 
 namespace {
 
@@ -671,6 +672,18 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
     off = align_up64(off + (uint64_t)seg.size() * 4, 256);
     h.off_rec = off;
     off = align_up64(off + n_records * 8, 256);
+    // Staging by global -> LDS copies: one DmaSlot per 16-byte slot of a window buffer's channel
+    // planes, 64 slots per copy.  The room is set aside whenever the plan's runs of four input
+    // words might qualify (decided below, once the staging table is written) and a wave would
+    // issue no more than kMaxDmaPerWave copies per chunk.
+    const int dma_copies = ceil_div((h.buf_floats - h.zero_floats) / 4, 64);
+    const bool dma_room = h.VW == 4 && !flat_runs && tiled_dma_staging_exists(h.K, h.Q, h.B) &&
+                          dma_copies <= kMaxDmaPerWave * h.WQ * h.WM;
+    h.n_dma = 0;
+    h.off_dma = off;
+    if (dma_room) off = align_up64(off + (uint64_t)h.n_tiles * dma_copies * 64 * sizeof(DmaSlot), 256);
+    h.off_zero = off;
+    off = align_up64(off + 64, 256);
     h.total_bytes = off;
     *bytes = (size_t)off;
     if (!out) return ESCOIN_OK;
@@ -740,7 +753,25 @@ int build_plan_once(const Dims& d, const int32_t* rowptr, const int32_t* stretch
         }
     }
     h.WW = wide_commit ? 4 : 1;
-    std::memcpy(base, &h, sizeof(h));  // the header once more, now with WW
+    // Every staged run lands on one aligned 16-byte slot: the same staging can be done by
+    // global -> LDS copies, slot by slot (slots without a run read zeros).
+    if (wide_commit && dma_room) {
+        h.n_dma = dma_copies;
+        DmaSlot* dma = (DmaSlot*)(base + h.off_dma);
+        const size_t per_tile = (size_t)dma_copies * 64;
+        for (size_t i = 0; i < (size_t)h.n_tiles * per_tile; ++i) { dma[i].src = -1; dma[i].chan = 0; }
+        for (int t = 0; t < h.n_tiles; ++t)
+            for (int j = 0; j < kMaxItemsPerThread; j += 4)
+                for (int tid = 0; tid < threads; ++tid) {
+                    const StageSlot& q = slots[((size_t)t * kMaxItemsPerThread + j) * threads + tid];
+                    if (q.src < 0) continue;
+                    const uint32_t byte = q.key & ((1u << kKeyOffsetBits) - 1);
+                    DmaSlot& ds = dma[(size_t)t * per_tile + byte / 16];
+                    ds.src = q.src;
+                    ds.chan = (int32_t)(q.key >> kKeyOffsetBits);
+                }
+    }
+    std::memcpy(base, &h, sizeof(h));  // the header once more, now with WW and n_dma
     std::memcpy(base + h.off_lanes, lanes.data(), lanes.size() * sizeof(LaneSlot));
     std::memcpy(base + h.off_perm, slot.data(), slot.size() * sizeof(RowSlot));
     std::memcpy(base + h.off_perm + slot.size() * sizeof(RowSlot), group_regions.data(), (size_t)h.n_mgroups * 4);

@@ -93,7 +93,19 @@ struct PlanHeader {
     int32_t max_regions; // most LDS regions (of WQ*Q*1024 bytes) a workgroup needs for partial sums
     int32_t MB;          // the channel groups are cut into MB blocks; the launch order is (block,
                          // tile, group in the block), so that an XCD meets 1/MB of the records
-    int32_t reserved[3];
+    int32_t n_dma;       // > 0: the window can also be staged without registers, by n_dma wave-wide
+                         // 16-byte global -> LDS copies per chunk (every 16-byte slot of a window
+                         // buffer is a run of four input words or zeros); 0: no such table
+    uint64_t off_dma;    // DmaSlot [n_tiles][n_dma][64]
+    uint64_t off_zero;   // 64 zero bytes: what the copy of a slot without input reads
 };
+
+// One 16-byte slot of a window buffer as the global -> LDS staging sees it: lane l of copy j
+// fills slot 64*j + l.
+struct DmaSlot {
+    int32_t src;    // like StageSlot::src for the slot's four words; -1 = the slot holds zeros
+    int32_t chan;   // channel inside the chunk
+};
+constexpr int kMaxDmaPerWave = 4;  // copies a wave issues per chunk at most (64 KB per chunk with 16 waves)
 
 }  // namespace escoin

@@ -38,6 +38,8 @@ struct TiledArgs {
     float* out;
     const float* bias;
     const StageSlot* stage;
+    const DmaSlot* dma;
+    const float* zero16;
     const LaneSlot* lanes;
     const int32_t* dst_lut;
     const RowSlot* slots;
@@ -48,7 +50,7 @@ struct TiledArgs {
     int N, C, HW, M, EF;
     int WM, WQ, CC, CC0, NB, CS, WW, MB;
     int n_tiles, n_mgroups, n_chunks, n_in_tiles;
-    int plane_stride, P4, n_items, buf_floats, tail_floats, rec_buf_bytes, region_floats, used_slots;
+    int plane_stride, P4, n_items, buf_floats, tail_floats, rec_buf_bytes, region_floats, used_slots, n_dma, win_slots;
     uint32_t flags;
 };
 
@@ -94,6 +96,19 @@ __device__ __forceinline__ void set_prio(int p) {
 
 constexpr uint32_t kKeyOffsetMask = (1u << kKeyOffsetBits) - 1;
 
+// Waits until at most n vector-memory operations of this wave are outstanding (and for every
+// LDS / scalar operation); n is wave-uniform.  The instruction takes an immediate.
+__device__ __forceinline__ void wait_vmcnt_at_most(int n) {
+    // simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14; expcnt is left alone (7)
+#define ESCOIN_WAIT(N) case N: __builtin_amdgcn_s_waitcnt(((N) & 15) | (7 << 4) | (((N) >> 4) << 14)); break;
+    switch (n) {
+        ESCOIN_WAIT(1) ESCOIN_WAIT(2) ESCOIN_WAIT(3) ESCOIN_WAIT(4) ESCOIN_WAIT(5) ESCOIN_WAIT(6) ESCOIN_WAIT(7)
+        ESCOIN_WAIT(8) ESCOIN_WAIT(9) ESCOIN_WAIT(10) ESCOIN_WAIT(11) ESCOIN_WAIT(12)
+        default: __builtin_amdgcn_s_waitcnt(0 | (7 << 4)); break;  // 0, or more than listed: everything
+    }
+#undef ESCOIN_WAIT
+}
+
 template <int B>
 struct Batch {
     u4 w[B / 2];  // B x {LDS byte offset, value bits}, two records per 16 bytes
@@ -118,6 +133,9 @@ constexpr int kRunStrideBytes = 62 * 16;
 // address arithmetic of its own (an immediate offset).
 // VW: input words per staging load (4: the plan dealt the window words in runs of four
 // consecutive, 16-byte aligned input words and the input pointer is 16-byte aligned; 1: any plan).
+// VW = 16: the window is not staged through registers at all; every 16-byte slot of a window
+// buffer is filled by a global -> LDS copy (a run of four input words, or zeros), which needs
+// the plan's DmaSlot table.
 template <int K, int Q, int B, int VW>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) void sconv_tiled_kernel(const TiledArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -164,11 +182,28 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     const int base0 = base_bytes[0];
 
     // ---- this thread's share of the staging work (the same for every chunk), from the plan
-    constexpr int kRuns = kMaxItemsPerThread / VW;
+    constexpr bool DMA = VW == 16;
+    constexpr int kRuns = DMA ? 1 : kMaxItemsPerThread / VW;
     int st_src[kRuns];  // per run of VW words: offset from the chunk's first input word, -1 = none
     // bits 0..17: LDS byte offset of the word inside a window buffer; 18..31: channel in the chunk
     uint32_t st_key[kMaxItemsPerThread];
-    {
+    // DMA staging: this wave issues the copies wave, wave + nwaves, ...; per copy, this lane's
+    // slot: where its four words come from (-1: zeros) and their channel inside the chunk
+    int dma_src[kMaxDmaPerWave], dma_chan[kMaxDmaPerWave];
+    const int nwaves = nthreads >> 6;
+    if (DMA) {
+        const int src_end = min(a.NB, a.N - n0) * a.C * a.HW;
+#pragma unroll
+        for (int i = 0; i < kMaxDmaPerWave; ++i) {
+            const int j = wave + i * nwaves;
+            DmaSlot v;
+            v.src = -1;
+            v.chan = 0;
+            if (j < a.n_dma) v = a.dma[((size_t)tile * a.n_dma + j) * 64 + lane];
+            dma_src[i] = v.src < src_end ? v.src : -1;
+            dma_chan[i] = v.chan;
+        }
+    } else {
         const StageSlot* __restrict__ sl = a.stage + (size_t)tile * kMaxItemsPerThread * nthreads + tid;
         // words of images past the end of the batch (ragged last image group) are not staged
         const int src_end = min(a.NB, a.N - n0) * a.C * a.HW;
@@ -203,8 +238,22 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         const int c0 = chunk_c0(ch);
         const int ccur = chunk_len(ch);
         const float* __restrict__ src = a.in + ((size_t)n0 * a.C + c0) * a.HW;
+        if (DMA) {
+            char* const win = lds_bytes + buf * win_bytes;
 #pragma unroll
-        for (int r = 0; r < kRuns; ++r)
+            for (int i = 0; i < kMaxDmaPerWave; ++i) {
+                const int j = wave + i * nwaves;  // wave-uniform
+                if (j < a.n_dma) {
+                    const bool has = dma_src[i] >= 0 && dma_chan[i] < ccur;
+                    const float* g = has ? src + dma_src[i] : a.zero16;
+                    if (j * 64 + lane < a.win_slots)  // lane 0 always passes: the copy is always issued
+                        __builtin_amdgcn_global_load_lds((const void*)g,
+                                                         (void __attribute__((address_space(3)))*)(win + 1024 * j), 16, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < (DMA ? 0 : kRuns); ++r)
             if (st_src[r] >= 0 && (int)(st_key[r * VW] >> kKeyOffsetBits) < ccur) {
                 if (VW == 4) {
                     const f4 v = *(const f4*)__builtin_assume_aligned(src + st_src[r], 16);
@@ -224,6 +273,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     };
     // Write the window words fetch(ch) loaded into window buffer `buf`.
     auto commit = [&](int ch, int buf) {
+        if (DMA) return;
         const int ccur = chunk_len(ch);
         char* const win = lds_bytes + buf * win_bytes;
         if (VW == 4 && a.WW == 4) {  // every run lands on 16 aligned, consecutive LDS bytes
@@ -258,19 +308,42 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
                 early_dst[q][i] = dd;
             }
     }
-    // The frame of zeros never changes: clear the window buffers and the tail once; from here
-    // on only words that hold input are rewritten, chunk after chunk.
-    for (int i = 4 * tid; i < 2 * a.buf_floats + a.tail_floats; i += 4 * nthreads)  // both are multiples of 4
-        *(f4*)__builtin_assume_aligned(&lds[i], 16) = (f4)(0.0f);
-    __syncthreads();
-    commit(cs, 0);
+    if (DMA) {
+        // The copies need no registers, so the second chunk is asked for right away as well:
+        // two chunks are on their way before the first FMA.  Every slot of the channel planes
+        // is rewritten by every chunk's copies (input or zeros); only the stretches behind
+        // them are cleared here, once.
+        if (!single_chunk) fetch(cs + a.CS, 1);
+        for (int i = 4 * a.win_slots + 4 * tid; i < a.buf_floats; i += 4 * nthreads)
+            *(f4*)__builtin_assume_aligned(&lds[i], 16) = (f4)(0.0f);
+        for (int i = a.buf_floats + 4 * a.win_slots + 4 * tid; i < 2 * a.buf_floats + a.tail_floats; i += 4 * nthreads)
+            *(f4*)__builtin_assume_aligned(&lds[i], 16) = (f4)(0.0f);
+        // Wait for the first chunk only.  The vector-memory counter counts down in issue order,
+        // so the first chunk is complete once no more operations are outstanding than this wave
+        // issued after it: its copies of the second chunk (window, then records), each of which
+        // is issued whatever the lanes do (lane 0 always takes part).
+        int later = 0;
+        if (!single_chunk) {
+            const int units = (int)blkp[2 * (cs + a.CS) + 1] * (B / 2);
+            later = (wave < a.n_dma ? (a.n_dma - wave + nwaves - 1) / nwaves : 0) +
+                    (units > wave * 64 ? (units - wave * 64 + nthreads - 1) / nthreads : 0);
+        }
+        wait_vmcnt_at_most(later);
+    } else {
+        // The frame of zeros never changes: clear the window buffers and the tail once; from
+        // here on only words that hold input are rewritten, chunk after chunk.
+        for (int i = 4 * tid; i < 2 * a.buf_floats + a.tail_floats; i += 4 * nthreads)  // both are multiples of 4
+            *(f4*)__builtin_assume_aligned(&lds[i], 16) = (f4)(0.0f);
+        __syncthreads();
+        commit(cs, 0);
+        __builtin_amdgcn_s_waitcnt(0);  // this wave's record copies have landed
+    }
     if (single_chunk) {  // the staging registers are free for good: they take the output offsets
 #pragma unroll
         for (int q = 0; q < Q; ++q)
 #pragma unroll
             for (int i = 0; i < 4; ++i) st_val[q * 4 + i] = __int_as_float(early_dst[q][i]);
     }
-    __builtin_amdgcn_s_waitcnt(0);  // this wave's record copies have landed
     __syncthreads();
 
     f4 acc[K][Q];
@@ -414,7 +487,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     int ch = cs, it = 0;
     for (; ch + a.CS < a.n_chunks; ch += a.CS, ++it) {
         const int buf = it & 1;
-        fetch(ch + a.CS, buf ^ 1);
+        if (!DMA || it > 0) fetch(ch + a.CS, buf ^ 1);  // (the copies of the second chunk are on their way)
         compute(ch, buf, std::false_type{});
         // The other buffers were last read in the previous iteration, which every wave left
         // through the barrier below: they can be rewritten now.
@@ -496,7 +569,13 @@ int allow_dynamic_lds(const void* kernel, int bytes) {
 // nine registers less; the ones the layers with W % 4 == 0 of the bundled workloads use).
 #define ESCOIN_TILED_WIDE_STAGING(X) X(1, 1, 2) X(2, 1, 2) X(4, 1, 2) X(2, 2, 2) X(4, 2, 2)
 
-TiledKernel pick(int K, int Q, int B, bool wide_staging) {
+TiledKernel pick(int K, int Q, int B, bool wide_staging, bool dma_staging) {
+    if (dma_staging) {
+#define ESCOIN_PICK(KK, QQ, BB) \
+    if (K == KK && Q == QQ && B == BB) return sconv_tiled_kernel<KK, QQ, BB, 16>;
+        ESCOIN_TILED_WIDE_STAGING(ESCOIN_PICK)
+#undef ESCOIN_PICK
+    }
     if (wide_staging) {
 #define ESCOIN_PICK(KK, QQ, BB) \
     if (K == KK && Q == QQ && B == BB) return sconv_tiled_kernel<KK, QQ, BB, 4>;
@@ -519,6 +598,9 @@ bool tiled_wide_staging_exists(int K, int Q, int B) {
 #undef ESCOIN_HAS
     return false;
 }
+
+// the same instantiations exist with global -> LDS staging
+bool tiled_dma_staging_exists(int K, int Q, int B) { return tiled_wide_staging_exists(K, Q, B); }
 
 bool tiled_variant_exists(int K, int Q, int B) {
 #define ESCOIN_HAS(KK, QQ, BB) \
@@ -547,7 +629,8 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
         h.stride != d.stride || h.pad != d.pad || h.E != d.E || h.F != d.F)
         return ESCOIN_EINVAL;
     // 16-byte staging loads need the plan's runs of four words and a 16-byte aligned input
-    TiledKernel kern = pick(h.K, h.Q, h.B, h.VW == 4 && ((uintptr_t)d_in & 15) == 0);
+    const bool aligned_in = ((uintptr_t)d_in & 15) == 0 && ((uintptr_t)d_plan & 15) == 0;
+    TiledKernel kern = pick(h.K, h.Q, h.B, h.VW == 4 && aligned_in, h.n_dma > 0 && h.VW == 4 && h.WW == 4 && aligned_in);
     if (!kern) return ESCOIN_EINVAL;
     const int threads = 64 * h.WQ * h.WM;
     if (threads > 1024 || threads <= 0) return ESCOIN_EINVAL;
@@ -558,7 +641,8 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
         h.n_chunks != (d.C <= h.CC0 ? 1 : 1 + (d.C - h.CC0 + h.CC - 1) / h.CC) ||
         h.WQ < 1 || h.WM < 1 || h.WS < 1 || h.WS > h.WM || h.tail_floats % 4 || h.rec_buf_bytes % 16 || h.front < 4 ||
         h.n_phases < 1 || h.n_phases > kMaxPhases || (h.VW != 1 && h.VW != 4) || (h.WW != 1 && h.WW != 4) || (h.WW == 4 && h.VW != 4) || h.CS < 1 || h.CS > h.n_chunks ||
-        h.zero_floats % 4 || h.zero_floats < h.P4 + 16 || h.MB < 1 || h.MB > 8 || h.MB > h.n_mgroups ||
+        h.zero_floats % 4 || h.zero_floats < h.P4 + 16 || h.n_dma < 0 ||
+        (h.n_dma > 0 && (h.n_dma != ((h.buf_floats - h.zero_floats) / 4 + 63) / 64 || h.n_dma > kMaxDmaPerWave * (threads / 64))) || h.MB < 1 || h.MB > 8 || h.MB > h.n_mgroups ||
         (long long)h.buf_floats != (long long)h.n_phases * h.CC * h.NB * h.plane_stride + h.zero_floats ||
         (long long)h.n_items * h.CC * h.NB > (long long)kMaxItemsPerThread * threads ||
         (long long)h.buf_floats * 4 >= (1 << kKeyOffsetBits) || h.max_regions < 0 ||
@@ -571,6 +655,10 @@ extern "C" int escoin_sconv_forward_tiled(const escoin_conv_desc* desc, const vo
     TiledArgs a;
     a.in = d_in; a.out = d_out; a.bias = d_bias;
     a.stage = (const StageSlot*)(base + h.off_items);
+    a.dma = (const DmaSlot*)(base + h.off_dma);
+    a.zero16 = (const float*)(base + h.off_zero);
+    a.n_dma = h.n_dma;
+    a.win_slots = (h.buf_floats - h.zero_floats) / 4;
     a.lanes = (const LaneSlot*)(base + h.off_lanes);
     a.dst_lut = (const int32_t*)(base + h.off_dst_lut);
     a.slots = (const RowSlot*)(base + h.off_perm);

@@ -70,6 +70,8 @@ class LayerRunner:
         if self.path == "tiled":
             h = self.plan_info
             vw = h["VW"] if self.d_in.data_ptr() % 16 == 0 else 1
+            if vw == 4 and h["n_dma"] > 0 and h["WW"] == 4:
+                vw = 16       # staged by global -> LDS copies
             return f"sconv_tiled_kernel<{h['K']}, {h['Q']}, {h['B']}, {vw}>"
         return "sconv_direct_kernel"
 

@@ -124,6 +124,22 @@ def simulate(plan: np.ndarray, x: np.ndarray, M: int) -> np.ndarray:
                 gsrc = (n0 * C + c0) * H * W + src[live]
                 assert gsrc.max(initial=0) < N * C * H * W, "staging reads past the end of the input"
                 lds[where // 4] = xflat[gsrc]
+                if h["n_dma"] > 0:
+                    # the same chunk staged by the global -> LDS copies: slot 64*j + lane of a
+                    # window buffer takes four consecutive input words, or zeros
+                    win_slots = (buf_floats - ZF) // 4
+                    assert h["n_dma"] == -(-win_slots // 64) and h["VW"] == 4 and h["WW"] == 4
+                    dma = plan[h["off_dma"]:h["off_dma"] + 8 * h["n_tiles"] * h["n_dma"] * 64].view(np.int32)
+                    dma = dma.reshape(h["n_tiles"], h["n_dma"] * 64, 2)[t][:win_slots]
+                    zero = plan[h["off_zero"]:h["off_zero"] + 64]
+                    assert not zero.any() and h["off_zero"] % 16 == 0 and h["off_dma"] % 16 == 0
+                    assert (dma[win_slots:, 0] < 0).all() if len(dma) > win_slots else True
+                    lds2 = np.zeros(lds_len)
+                    for sl in np.nonzero((dma[:, 0] >= 0) & (dma[:, 0] < nb * C * H * W) & (dma[:, 1] < ccur))[0]:
+                        g0 = (n0 * C + c0) * H * W + int(dma[sl, 0])
+                        assert g0 % 4 == 0 and g0 + 4 <= N * C * H * W
+                        lds2[4 * sl:4 * sl + 4] = xflat[g0:g0 + 4]
+                    assert np.array_equal(lds, lds2), "the two staging tables disagree"
                 for b in range(bins):
                     mgi = b // WM
                     assert seg[b, ch, 0] + seg[b, ch, 1:].sum() <= blk[mgi, ch, 1]
