@@ -192,17 +192,11 @@ def main():
                                      for L, r in zip(layers, runners)]}))
         return
 
-    # ---- value: wall clock over the timed steps (warm)
-    sec_per_step = wall_time(torch, runners, args.steps, args.warmup)
-    ms_per_step = sec_per_step * 1e3
-    value = sum(flops) / sec_per_step / 1e9
-
-    # ---- per-kernel durations, warm: a second run of the same steps with events
-    dur = time_kernels(torch, runners, args.steps, stream)
-    avg_ms, med_ms = dur.mean(axis=0), np.median(dur, axis=0)
     # ---- cold: every step starts from flushed caches (at least 20 steps for the median)
     cold_ms = None
     if not args.no_cold:
+        for r in runners:
+            r.run()
         flush = torch.zeros(FLUSH_BYTES // 4, dtype=torch.float32, device="cuda")
         cold_ms = np.median(time_kernels(torch, runners, max(20, min(args.steps, 50)), stream, flush), axis=0)
         del flush
@@ -219,6 +213,16 @@ def main():
                 r.run()
         two = np.median(time_kernels(torch, direct, n2, stream), axis=0).reshape(len(layers), 2)
         del direct
+
+    # ---- value: W warm-up steps, then the wall clock over exactly K steps (warm).  The legs above
+    # have run before it, so the clocks have left their idle state when the warm-up starts.
+    sec_per_step = wall_time(torch, runners, args.steps, args.warmup)
+    ms_per_step = sec_per_step * 1e3
+    value = sum(flops) / sec_per_step / 1e9
+
+    # ---- per-kernel durations, warm: a second run of the same steps with events
+    dur = time_kernels(torch, runners, args.steps, stream)
+    avg_ms, med_ms = dur.mean(axis=0), np.median(dur, axis=0)
 
     rows, i = [], 0
     for li, (L, r, fl) in enumerate(zip(layers, runners, flops)):
