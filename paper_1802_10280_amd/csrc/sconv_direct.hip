@@ -19,12 +19,29 @@ __global__ __launch_bounds__(kThreads) void sconv_direct_kernel(
     const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
     const float* __restrict__ value, const float* __restrict__ padded, float* __restrict__ out,
     const float* __restrict__ bias, uint32_t flags, int N, int M, int E, int F, int Wp, int stride,
-    int img_elems /* C*Hp*Wp */, int group_images) {
-    const int m = blockIdx.y;
+    int img_elems /* C*Hp*Wp */, int group_images, int n_groups, int bx, int deal) {
+    // Workgroup -> (image group, output channel, block of positions), all channels of a group
+    // before the next group.  Consecutive workgroup ids land on different XCDs (id mod 8), each
+    // with an L2 of its own.  Small images: the XCDs share every group (plain order).  Large
+    // images (`deal`): the groups are dealt to the XCDs in turn and an XCD walks its own groups
+    // one after the other, so that the few groups it has in flight stay in its L2.
+    const uint32_t per_group = (uint32_t)bx * (uint32_t)M;
+    uint32_t group, rest;
+    if (deal) {
+        const uint32_t xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        group = (slot / per_group) * 8 + xcd;
+        rest = slot % per_group;
+    } else {
+        group = blockIdx.x / per_group;
+        rest = blockIdx.x % per_group;
+    }
+    if (group >= (uint32_t)n_groups) return;
+    const int m = (int)(rest / (uint32_t)bx);
+    const uint32_t xblk = rest % (uint32_t)bx;
     const int EF = E * F;
     const int j0 = rowptr[m], j1 = rowptr[m + 1];
     const float b = (flags & ESCOIN_F_BIAS) ? bias[m] : 0.0f;
-    const int n_first = blockIdx.z * group_images;
+    const int n_first = (int)group * group_images;
     const int n_here = min(group_images, N - n_first);
     const uint32_t positions = (uint32_t)n_here * (uint32_t)EF;
     const float* __restrict__ grp = padded + (size_t)n_first * img_elems;
@@ -32,7 +49,7 @@ __global__ __launch_bounds__(kThreads) void sconv_direct_kernel(
     float acc[kPix];
 #pragma unroll
     for (int k = 0; k < kPix; ++k) {
-        p[k] = (blockIdx.x * kPix + k) * kThreads + threadIdx.x;
+        p[k] = (xblk * kPix + k) * kThreads + threadIdx.x;
         const uint32_t pc = p[k] < positions ? p[k] : 0;  // clamp: out-of-range lanes read a valid pixel
         const uint32_t n = pc / (uint32_t)EF, pp = pc - n * (uint32_t)EF;
         const uint32_t h = pp / (uint32_t)F, w = pp - h * (uint32_t)F;
@@ -69,28 +86,31 @@ int launch_sconv_direct(const Dims& d, const int32_t* d_rowptr, const int32_t* d
     // offset below img_elems) and position numbers stay under 2^32
     long long limit = std::max<long long>(1, std::min<long long>(d.N, ((1ll << 31) / img_elems)));
     limit = std::max<long long>(1, std::min<long long>(limit, (1ll << 30) / EF));
-    // A group's padded input should stay in the L2s (4 MB per XCD) while all M output channels
-    // walk over it (the grid's slowest index is the group), yet its positions should fill the
-    // lanes of whole workgroups: among the group sizes up to 6 MB of input, the one that wastes
-    // the fewest lanes (the smaller one within 3 %).
+    // A group's padded input should stay in an L2 (4 MB per XCD) while all M output channels
+    // walk over it, and its positions should fill the lanes of whole workgroups.  Images of
+    // more than 512 KB (eight of them in flight overflow an L2) are dealt to the XCDs, and the
+    // groups should then come in multiples of 8.  Among the sizes that split the batch evenly
+    // and hold at most 6 MB of input: the best lane fill (x XCD balance), ties to the smaller.
     const long long per_block = kThreads * kPix;
+    const bool deal = img_elems * 4 > (512ll << 10);
     const long long most = std::max<long long>(1, std::min<long long>(limit, (6ll << 20) / (img_elems * 4)));
     long long group = 1;
-    double best_fill = 0.0;
+    double best = 0.0;
     for (long long g = 1; g <= most; ++g) {
-        const long long n_groups = (d.N + g - 1) / g, even = (d.N + n_groups - 1) / n_groups;
-        if (even != g) continue;  // only sizes that split the batch evenly
+        const long long n_g = (d.N + g - 1) / g, even = (d.N + n_g - 1) / n_g;
+        if (even != g) continue;
         const double fill = (double)(g * EF) / (double)(((g * EF + per_block - 1) / per_block) * per_block);
-        if (fill > best_fill * 1.03) { best_fill = fill; group = g; }
+        const double balance = deal ? (double)n_g / (double)(((n_g + 7) / 8) * 8) : 1.0;
+        if (fill * balance > best * 1.03) { best = fill * balance; group = g; }
     }
     const long long groups = (d.N + group - 1) / group;
     const long long bx = (group * EF + per_block - 1) / per_block;
-    // grid.y / grid.z carry M and the image groups; reject rather than fold silently
-    if (d.M > 65535 || groups > 65535 || bx > 0x7FFFFFFFll) return ESCOIN_ERANGE;
-    dim3 grid((unsigned)bx, d.M, (unsigned)groups);
-    return launch(sconv_direct_kernel, grid, dim3(kThreads), 0, stream, d_rowptr, d_colidx, d_value,
-                  d_padded, d_out, d_bias, flags, d.N, d.M, d.E, d.F, d.Wp, d.stride,
-                  (int)img_elems, (int)group);
+    // one-dimensional grid: 8 XCDs x (groups per XCD) x M x blocks of positions
+    const long long blocks = (deal ? 8 * ((groups + 7) / 8) : groups) * bx * d.M;
+    if (blocks > 0x7FFFFFFFll || bx * d.M > 0x7FFFFFFFll) return ESCOIN_ERANGE;
+    return launch(sconv_direct_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_rowptr, d_colidx,
+                  d_value, d_padded, d_out, d_bias, flags, d.N, d.M, d.E, d.F, d.Wp, d.stride,
+                  (int)img_elems, (int)group, (int)groups, (int)bx, (int)deal);
 }
 
 }  // namespace escoin
