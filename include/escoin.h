@@ -159,12 +159,18 @@ int escoin_sconv_plan_build(const escoin_conv_desc *desc, const int32_t *rowptr,
  *   d_out      device, N*M*E*F floats, overwritten
  * ESCOIN_EINVAL if the plan was built for another layer geometry.
  *
- * A plan with CS > 1 (chosen by default only when the batch is too small to give every compute
- * unit a workgroup otherwise) splits the input channels of a tile over CS workgroups.  The call
- * then enqueues three kernels instead of one: a zero fill of d_out, the convolution, whose
- * workgroups add their partial sums with fp32 atomics (the order of those additions, and with
- * it the last bits of the result, may differ from run to run), and, with ESCOIN_F_RELU, the
- * clamp as a pass of its own.
+ * By default a launch that would leave compute units idle (small batches) splits every output
+ * channel's nonzeros over several waves of a workgroup and adds their partial sums on chip: one
+ * kernel, and the same bits on every run.
+ *
+ * A plan with CS > 1 (only on request, through the tuning) splits the input channels of a tile
+ * over CS workgroups instead.  The call then enqueues three kernels: a zero fill of d_out, the
+ * convolution, whose workgroups add their partial sums with fp32 atomics (the order of those
+ * additions, and with it the last bits of the result, may differ from run to run), and, with
+ * ESCOIN_F_RELU, the clamp as a pass of its own.
+ *
+ * d_in and d_plan that are 16-byte aligned let the kernel stage with 16-byte loads (or with
+ * global -> LDS copies); any 4-byte aligned pointer is accepted.
  */
 int escoin_sconv_forward_tiled(const escoin_conv_desc *desc, const void *plan_host,
                                const void *d_plan, const float *d_in, float *d_out,

@@ -1,24 +1,28 @@
 // LDS-tiled sconv for gfx950.
 //
 // One workgroup owns a tile of output positions (a band of rows of one image, or several
-// small images) and a group of output channels, and walks the input channels in chunks:
-//   stage   the chunk's input window goes from the UNPADDED input to LDS through a table of
-//           (input word -> LDS word); the frame of zeros is written once at kernel start and
-//           never touched again, so pad_in is folded into the staging.  The window is the
-//           flat padded array of Section 3.1, one plane per stride phase.  The chunk's CSR
+// small images) and a group of accumulator rows, and walks the input channels in chunks:
+//   stage   the chunk's input window goes from the UNPADDED input to LDS: the window is the flat
+//           padded array of Section 3.1, one plane per stride phase, and its frame of zeros is
+//           never fetched, so pad_in is folded into the staging.  Either through registers and
+//           a table of (input word -> LDS word), the frame being cleared once at kernel start;
+//           or, where every run of four input words lands on one aligned 16-byte LDS slot, by
+//           global -> LDS copies that fill every slot with input or with zeros.  The chunk's CSR
 //           records (LDS offset, value) of the workgroup's rows are copied to LDS as well
-//           (Section 3.3 keeps colidx/value on chip).  Both are double-buffered: the global
-//           loads of chunk i+1 are issued before chunk i is consumed (window words wait in
-//           registers, records go global -> LDS directly), so there is one barrier per chunk;
-//   compute Algorithm 2 on that window: a wave walks the records of its K CSR rows (every
-//           lane reads the same record: an LDS broadcast); a lane owns 4 consecutive
+//           (Section 3.3 keeps colidx/value on chip).  Both are double-buffered: chunk i+1 is on
+//           its way while chunk i is consumed, with one barrier per chunk;
+//   compute Algorithm 2 on that window: a wave walks the records of its K accumulator rows
+//           (every lane reads the same record: an LDS broadcast); a lane owns 4 consecutive
 //           positions of the flat array per position run.  For each record it fetches the
 //           aligned 16 bytes that hold most of the four words val multiplies; the words that
 //           fall into the neighbouring 16-byte group are taken from the neighbouring lane,
 //           which has just fetched them, with a lane shift (DPP) instead of a second LDS
 //           read.  Records are grouped by that alignment class so the shift is static code;
 //   store   positions that are real outputs go to out[n][m][h][w] through the second table,
-//           with the optional bias + ReLU epilogue.
+//           with the optional bias + ReLU epilogue: a row that is whole in its wave as soon as
+//           the wave has finished it in the last chunk; an output channel whose nonzeros are
+//           split over several accumulator rows (of different waves) after its partial sums
+//           have met in LDS.
 // Consecutive lanes own consecutive positions (the data-to-thread mapping of Section 3.2), so
 // LDS reads are conflict-free and output stores are contiguous along w.
 #include <algorithm>

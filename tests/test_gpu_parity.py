@@ -230,7 +230,7 @@ def test_tiled_buffers_that_are_only_4_byte_aligned(oracle):
     must give way to 4-byte ones (W and F are multiples of 4 here, so they would be used)."""
     import torch
     print("sconv tiled misaligned buffers", flush=True)
-    L = wl.custom_layer(2, 6, 16, 16, 8, 3, 3, 1, 1, 0.6, seed=77, dist="normal")
+    L = wl.custom_layer(2, 8, 24, 24, 8, 3, 3, 1, 1, 0.6, seed=77, dist="normal")
     dl = DeviceLayer(esc, L)
     ref, bound = oracle_full(oracle, L, esc.F_BIAS)
     assert_within_bound(dl.forward_tiled(esc.F_BIAS), ref, bound, "aligned")
@@ -245,6 +245,23 @@ def test_tiled_buffers_that_are_only_4_byte_aligned(oracle):
     got = d_out.cpu().numpy().reshape(ref.shape)
     assert_within_bound(got, ref, bound, "misaligned")
     assert torch.isnan(big_out[0]) and torch.isnan(big_out[1 + n_out:]).all()   # nothing written outside
+    # the aligned call staged by global -> LDS copies, this one word by word through registers:
+    # the same sums in the same order
+    assert esc.plan_header(dl.plan)["n_dma"] > 0
+    assert got.tobytes() == dl.forward_tiled(esc.F_BIAS).tobytes()
+
+
+def test_small_batch_default_is_one_launch_with_the_same_bits_every_run(oracle):
+    """Batch 1: the default plan splits every channel over waves of a workgroup (no atomics), so
+    two runs agree bit for bit."""
+    print("sconv tiled batch 1 determinism", flush=True)
+    L = wl.make_layer("A1b1")
+    dl = DeviceLayer(esc, L)
+    a = dl.forward_tiled(esc.F_BIAS | esc.F_RELU)
+    h = esc.plan_header(dl.plan)
+    assert h["CS"] == 1 and h["WS"] > 1 and h["max_regions"] > 0
+    for _ in range(3):
+        assert dl.forward_tiled(esc.F_BIAS | esc.F_RELU).tobytes() == a.tobytes()
 
 
 # Shapes outside the bundled workloads, in the plan's default tiling: first layers of the
