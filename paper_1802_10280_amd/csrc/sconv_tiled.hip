@@ -67,24 +67,37 @@ typedef const int32_t __attribute__((address_space(4))) * ci32p;
 __device__ __forceinline__ cu32p as_const(const uint32_t* p) { return (cu32p)(uintptr_t)p; }
 __device__ __forceinline__ ci32p as_const(const int32_t* p) { return (ci32p)(uintptr_t)p; }
 
-// Value of `v` in the next lane (lane 63 gets 0) / in the previous lane (lane 0 gets 0).
-__device__ __forceinline__ float from_next_lane(float v) {
-    return __builtin_bit_cast(
-        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x130 /* wave_shl:1 */, 0xF, 0xF, true));
+// acc += w * (x of the next lane) / (x of the previous lane): the lane shift rides on the
+// multiply-add itself (its DPP form), so the neighbour's word costs no instruction of its own.
+// A lane with no such neighbour (63, resp. 0) multiplies a zero.  The shifted operand comes
+// straight from an LDS read; nothing here writes it with a vector instruction, which that form
+// would need two idle issue slots after.
+__device__ __forceinline__ float fma_next_lane(float acc, float x, float w) {
+    asm("v_fmac_f32_dpp %0, %1, %2 wave_shl:1 row_mask:0xf bank_mask:0xf bound_ctrl:0" : "+v"(acc) : "v"(x), "v"(w));
+    return acc;
 }
-__device__ __forceinline__ float from_prev_lane(float v) {
-    return __builtin_bit_cast(
-        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x138 /* wave_shr:1 */, 0xF, 0xF, true));
+__device__ __forceinline__ float fma_prev_lane(float acc, float x, float w) {
+    asm("v_fmac_f32_dpp %0, %1, %2 wave_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:0" : "+v"(acc) : "v"(x), "v"(w));
+    return acc;
 }
 
-// The four words a record of alignment class CLS multiplies, given the aligned group `x` this
-// lane fetched (its neighbours fetched the adjacent groups at the same time).
+// acc += w * (the four words a record of alignment class CLS multiplies), given the aligned
+// group `x` this lane fetched (its neighbours fetched the adjacent groups at the same time).
 template <int CLS>
-__device__ __forceinline__ f4 window_words(f4 x) {
-    if (CLS == 0) return x;
-    if (CLS == 1) return (f4){x[1], x[2], x[3], from_next_lane(x[0])};
-    if (CLS == 2) return (f4){x[2], x[3], from_next_lane(x[0]), from_next_lane(x[1])};
-    return (f4){from_prev_lane(x[3]), x[0], x[1], x[2]};
+__device__ __forceinline__ void fma_window(f4& acc, f4 x, float w) {
+    if (CLS == 0) {
+        acc += w * x;
+    } else if (CLS == 1) {
+        acc[0] += w * x[1]; acc[1] += w * x[2]; acc[2] += w * x[3];
+        acc[3] = fma_next_lane(acc[3], x[0], w);
+    } else if (CLS == 2) {
+        acc[0] += w * x[2]; acc[1] += w * x[3];
+        acc[2] = fma_next_lane(acc[2], x[0], w);
+        acc[3] = fma_next_lane(acc[3], x[1], w);
+    } else {
+        acc[0] = fma_prev_lane(acc[0], x[3], w);
+        acc[1] += w * x[0]; acc[2] += w * x[1]; acc[3] += w * x[2];
+    }
 }
 
 // Issue priority of this wave (0..3, higher is served first); `p` folds to a constant once the
@@ -453,7 +466,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
             for (int u = 0; u < B; ++u)
 #pragma unroll
                 for (int q = 0; q < Q; ++q)
-                    ak[q] += __uint_as_float(cur.w[u >> 1][(u & 1) * 2 + 1]) * window_words<CLS>(x[u][q]);
+                    fma_window<CLS>(ak[q], x[u][q], __uint_as_float(cur.w[u >> 1][(u & 1) * 2 + 1]));
         };
         auto run_class = [&](auto cls_tag, f4(&ak)[Q], int cnt) {
             int b = 0;
