@@ -13,7 +13,7 @@ Prints ONE JSON line:
   layers           per layer: mean and median kernel time warm, median cold (caches flushed by a
                    large write before every step), both roofline fractions, and the paper's
                    two-kernel dataflow (pad_in, then sconv on the padded array) timed beside it;
-  other_workloads  the remaining bundled workloads, shorter runs of the same measurement;
+  other_workloads  the remaining bundled workloads, shorter runs (100 steps) of the same measurement;
   cpu_baseline     the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -317,8 +317,10 @@ def main():
             fl_w = esc.F_BIAS | esc.F_RELU if w == "chain" else args.flags
             ns, ls, rs = make_runners(wl, LayerRunner, w, args.path, fl_w)
             fl = [2.0 * L.nnz * L.spec.E * L.spec.F * L.spec.N for L in ls]
-            sec = wall_time(torch, rs, 50, 5)
-            med = np.median(time_kernels(torch, rs, 30, stream), axis=0)
+            # building the plans on the host has let the clocks drop: a longer warm-up than the
+            # steps themselves would need
+            sec = wall_time(torch, rs, 100, 40)
+            med = np.median(time_kernels(torch, rs, 50, stream), axis=0)
             per, j = {}, 0
             for L, r in zip(ls, rs):
                 n_k = len(r.kernel_names())

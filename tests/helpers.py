@@ -111,3 +111,34 @@ def seam_points(spec, plan_info, seed, pairs=24):
             for m in rng.integers(0, spec.M, size=max(1, pairs // 4)):
                 pts += [(n, int(m), h, w) for h in range(spec.E) for w in range(spec.F)]
     return np.array(pts, dtype=np.int32).reshape(-1, 4)
+
+
+def random_layers_and_tunings(wl, seed, count):
+    """Seeded random small layers (any filter size, stride, padding) with random tiling knobs."""
+    rng = np.random.default_rng(seed)
+    for it in range(count):
+        R, S = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        stride, pad = int(rng.choice([1, 1, 1, 2, 3])), int(rng.integers(0, 4))
+        H = int(rng.integers(max(1, R - 2 * pad), 20))
+        W = int(rng.integers(max(1, S - 2 * pad), 30))
+        N, C, M = int(rng.integers(1, 9)), int(rng.integers(1, 7)), int(rng.integers(1, 10))
+        L = wl.custom_layer(N, C, H, W, M, R, S, stride, pad, float(rng.choice([0.0, 0.5, 0.9])),
+                            seed=5000 + it, dist="normal")
+        tune = {}
+        if rng.random() < 0.7:
+            tune["K"], tune["Q"] = [(1, 1), (1, 2), (2, 1), (2, 2), (4, 1), (4, 2), (8, 1)][int(rng.integers(0, 7))]
+        if rng.random() < 0.5:
+            tune["WM"] = int(rng.integers(1, 5))
+        if rng.random() < 0.5:
+            tune["CC"] = int(rng.integers(1, C + 1))
+        if rng.random() < 0.4:
+            tune["NB"] = int(rng.integers(1, N + 1))
+        elif rng.random() < 0.4:
+            tune["TH"] = int(rng.integers(1, L.spec.E + 1))
+        if rng.random() < 0.3:
+            tune["CS"] = int(rng.integers(1, 4))
+        if rng.random() < 0.4:
+            tune["WS"] = int(rng.integers(1, 5))
+        if rng.random() < 0.3:
+            tune["CC0"] = int(rng.integers(1, C + 1))
+        yield L, tune

@@ -9,7 +9,8 @@ import pytest
 import paper_1802_10280_amd as esc
 from paper_1802_10280_amd import workloads as wl
 
-from helpers import DeviceLayer, assert_within_bound, oracle_full, sample_points, seam_points, to_dev
+from helpers import (DeviceLayer, assert_within_bound, oracle_full, random_layers_and_tunings, sample_points,
+                     seam_points, to_dev)
 
 pytestmark = pytest.mark.gpu
 
@@ -80,6 +81,25 @@ def test_sconv_matches_oracle_small(oracle, cfg, path):
         got = dl.run(path, flags)
         ref, bound = oracle_full(oracle, L, flags)
         assert_within_bound(got, ref, bound, f"{path} {cfg} flags={flags}")
+
+
+def test_random_layers_and_tilings(oracle):
+    """The seeded random layers and knobs whose plans the CPU suite replays (there with every
+    staged read checked against the bounds of the input): both kernels against the oracle."""
+    done = 0
+    for L, tune in random_layers_and_tunings(wl, 20260, 90):
+        print("sconv random", L.spec, tune, flush=True)
+        ref, bound = oracle_full(oracle, L, esc.F_BIAS)
+        try:
+            dl = DeviceLayer(esc, L, tuning=tune)
+            got = dl.forward_tiled(esc.F_BIAS)
+        except esc.EscoinError as e:
+            assert e.code in (esc.ERANGE, esc.EINVAL), (L.spec, tune)   # a tiling that cannot be realised
+            continue
+        assert_within_bound(got, ref, bound, f"tiled {L.spec} {tune}")
+        assert_within_bound(dl.run("direct", esc.F_BIAS), ref, bound, f"direct {L.spec}")
+        done += 1
+    assert done >= 70
 
 
 TUNINGS = [

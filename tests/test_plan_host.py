@@ -7,6 +7,7 @@ import pytest
 import paper_1802_10280_amd as esc
 from paper_1802_10280_amd import workloads as wl
 
+from helpers import random_layers_and_tunings
 from plan_sim import simulate
 
 CASES = [
@@ -67,33 +68,9 @@ def test_plan_replay_matches_oracle(oracle, cfg, tune):
 def test_random_layers_and_tilings_replay(oracle):
     """Seeded random small layers (any filter size, stride, padding) with random knobs: every
     plan the builder accepts must replay to the oracle's result."""
-    rng = np.random.default_rng(20260)
     done = 0
-    for it in range(90):
-        R, S = int(rng.integers(1, 8)), int(rng.integers(1, 8))
-        stride, pad = int(rng.choice([1, 1, 1, 2, 3])), int(rng.integers(0, 4))
-        H = int(rng.integers(max(1, R - 2 * pad), 20))
-        W = int(rng.integers(max(1, S - 2 * pad), 30))
-        N, C, M = int(rng.integers(1, 9)), int(rng.integers(1, 7)), int(rng.integers(1, 10))
-        L = wl.custom_layer(N, C, H, W, M, R, S, stride, pad, float(rng.choice([0.0, 0.5, 0.9])),
-                            seed=5000 + it, dist="normal")
-        tune = {}
-        if rng.random() < 0.7:
-            tune["K"], tune["Q"] = [(1, 1), (1, 2), (2, 1), (2, 2), (4, 1), (4, 2), (8, 1)][int(rng.integers(0, 7))]
-        if rng.random() < 0.5:
-            tune["WM"] = int(rng.integers(1, 5))
-        if rng.random() < 0.5:
-            tune["CC"] = int(rng.integers(1, C + 1))
-        if rng.random() < 0.4:
-            tune["NB"] = int(rng.integers(1, N + 1))
-        elif rng.random() < 0.4:
-            tune["TH"] = int(rng.integers(1, L.spec.E + 1))
-        if rng.random() < 0.3:
-            tune["CS"] = int(rng.integers(1, 4))
-        if rng.random() < 0.4:
-            tune["WS"] = int(rng.integers(1, 5))
-        if rng.random() < 0.3:
-            tune["CC0"] = int(rng.integers(1, C + 1))
+    for L, tune in random_layers_and_tunings(wl, 20260, 90):
+        R, S, C, M, stride, pad = L.spec.R, L.spec.S, L.spec.C, L.spec.M, L.spec.stride, L.spec.pad
         d = esc.desc_of(L.spec)
         st = esc.escoin_sconv_pack(d, L.rowptr, L.colidx)
         try:
